@@ -1,0 +1,320 @@
+/*
+ * krul_oracle.c -- TEST INFRASTRUCTURE, not product code.
+ *
+ * A plain, slow, fp64 CPU statement of what the cross-layer attention-similarity
+ * estimator and the layer-pair selector of Krul (arxiv 2507.08045) compute.  It
+ * exists so that tests, the smoke check and the benchmark's cpu_baseline leg have
+ * something independent to compare the GPU library with.  Nothing in the product
+ * path may include, link or call this file, and this file shares no code, header
+ * or table with the GPU library.
+ *
+ * What is computed, and from which passage:
+ *   - attention weights  softmax(Q K^T / sqrt(d_K))            (Sec. 2.1, the
+ *     attention equation), one full Tq x S matrix per (layer, head), stored;
+ *   - per query row, the similarity of the two rows that two adjacent layers
+ *     give the same token: cosine (the measure named in the caption of the
+ *     layer-similarity figure, Fig. 3) and the Euclidean distance (Alg. 1,
+ *     "Euclidean_Distance", and Sec. 4.2), the latter as a plain difference,
+ *     never through the a^2+b^2-2ab expansion of Sec. 7;
+ *   - token-wise aggregation (Sec. 5; Sec. 7 "adds up"): mean over query rows,
+ *     then the average over heads (Sec. 4.2 "average distance");
+ *   - the greedy disjoint pair choice of Alg. 1 (sort by similarity, skip a pair
+ *     if either layer is already shared, stop at the budget) (Sec. 4.2);
+ *   - the input-insensitive ("I-R") layer test of Sec. 4.2 / Alg. 1, first loop:
+ *     mean attention mass on the first and last tenth of the history.
+ *
+ * Readings taken where the paper leaves a choice (adjacent pairs only, row-wise
+ * similarity then mean, grouped-query head mapping h -> h / (Hq/Hkv), no mask
+ * between query tokens, stable tie-break on the lower layer index) are listed in
+ * the design notes of the repository; each is marked below where it is applied.
+ *
+ * Every function here is pinned by tests that do not re-use this code: closed
+ * forms (uniform keys, S = 1, S = 2, one-hot limit), invariants (identical
+ * layers, shift, permutation, pair symmetry, GQA == repeated MHA), library
+ * routines (scipy softmax / cdist) on small inputs, the Gaussian large-S limit,
+ * and exhaustive simulation of Alg. 1 for the selector.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+typedef struct {
+    int32_t batch, n_layers, n_q_heads, n_kv_heads, head_dim, n_hist, n_query;
+    int32_t dtype;   /* ORACLE_F32 or ORACLE_BF16 (raw 16-bit patterns) */
+    double scale;    /* <= 0 means 1/sqrt(head_dim)  (Sec. 2.1) */
+} oracle_shape_t;
+
+/* Exact widening of one stored element to double. */
+static double elem(const void *p, int dtype, size_t i)
+{
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)p)[i];
+    uint32_t bits = (uint32_t)((const uint16_t *)p)[i] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static double eff_scale(const oracle_shape_t *s)
+{
+    return s->scale > 0.0 ? s->scale : 1.0 / sqrt((double)s->head_dim);
+}
+
+/*
+ * Attention weights of layer l, query head h of conversation b: P[t*S + j],
+ * t < Tq, j < S.  Sec. 2.1: softmax over the keys of (q . k) / sqrt(d_K).
+ * Query head h reads kv head h / (Hq/Hkv) (grouped-query reading).  No mask:
+ * every query row sees all S history keys.
+ */
+static void attention_weights(const oracle_shape_t *s, const void *q, const void *k,
+                              int b, int l, int h, double *P)
+{
+    const int d = s->head_dim, S = s->n_hist, Tq = s->n_query;
+    const int g = s->n_q_heads / s->n_kv_heads;
+    const int hk = h / g;
+    const double sc = eff_scale(s);
+    const size_t qbase = ((((size_t)b * s->n_layers + l) * s->n_q_heads + h) * (size_t)Tq) * d;
+    const size_t kbase = ((((size_t)b * s->n_layers + l) * s->n_kv_heads + hk) * (size_t)S) * d;
+    double *qrow = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int t = 0; t < Tq; ++t) {
+        double *row = P + (size_t)t * S;
+        for (int i = 0; i < d; ++i)
+            qrow[i] = elem(q, s->dtype, qbase + (size_t)t * d + i);
+        double mx = -INFINITY;
+        for (int j = 0; j < S; ++j) {
+            double acc = 0.0;
+            for (int i = 0; i < d; ++i)
+                acc += qrow[i] * elem(k, s->dtype, kbase + (size_t)j * d + i);
+            row[j] = acc * sc;
+            if (row[j] > mx) mx = row[j];
+        }
+        double z = 0.0;
+        for (int j = 0; j < S; ++j) {
+            row[j] = exp(row[j] - mx);
+            z += row[j];
+        }
+        for (int j = 0; j < S; ++j)
+            row[j] /= z;
+    }
+    free(qrow);
+}
+
+/*
+ * One (conversation b, pair l -> (l, l+1), query head h) unit: mean over the
+ * query rows of the cosine similarity and of the Euclidean distance between
+ * the two layers' attention rows.
+ */
+static void unit_scores(const oracle_shape_t *s, const void *q, const void *k,
+                        int b, int l, int h, double *cos_mean, double *dist_mean)
+{
+    const int S = s->n_hist, Tq = s->n_query;
+    double *Pa = (double *)malloc(sizeof(double) * (size_t)Tq * S);
+    double *Pb = (double *)malloc(sizeof(double) * (size_t)Tq * S);
+    attention_weights(s, q, k, b, l, h, Pa);
+    attention_weights(s, q, k, b, l + 1, h, Pb);
+    double csum = 0.0, dsum = 0.0;
+    for (int t = 0; t < Tq; ++t) {
+        const double *a = Pa + (size_t)t * S, *c = Pb + (size_t)t * S;
+        double ab = 0.0, aa = 0.0, bb = 0.0, dd = 0.0;
+        for (int j = 0; j < S; ++j) {
+            ab += a[j] * c[j];
+            aa += a[j] * a[j];
+            bb += c[j] * c[j];
+            const double df = a[j] - c[j];
+            dd += df * df;
+        }
+        csum += ab / (sqrt(aa) * sqrt(bb));
+        dsum += sqrt(dd);
+    }
+    *cos_mean = csum / Tq;
+    *dist_mean = dsum / Tq;
+    free(Pa);
+    free(Pb);
+}
+
+static int shape_ok(const oracle_shape_t *s)
+{
+    return s && s->batch > 0 && s->n_layers >= 2 && s->n_q_heads > 0 && s->n_kv_heads > 0 &&
+           s->n_q_heads % s->n_kv_heads == 0 && s->head_dim > 0 && s->n_hist > 0 &&
+           s->n_query > 0 && (s->dtype == ORACLE_F32 || s->dtype == ORACLE_BF16);
+}
+
+/*
+ * Scores of a chosen list of units.  units[3*u + {0,1,2}] = (b, l, h).
+ * head_cos[u], head_dist[u] receive the token means.  Returns 0, or -1 on a bad
+ * argument.  Units are independent; they are spread over the host threads.
+ */
+int krul_oracle_units(const oracle_shape_t *s, const void *q, const void *k,
+                      int n_units, const int32_t *units, double *head_cos, double *head_dist)
+{
+    if (!shape_ok(s) || !q || !k || n_units < 0 || (n_units && (!units || !head_cos || !head_dist)))
+        return -1;
+    for (int u = 0; u < n_units; ++u) {
+        const int b = units[3 * u], l = units[3 * u + 1], h = units[3 * u + 2];
+        if (b < 0 || b >= s->batch || l < 0 || l >= s->n_layers - 1 || h < 0 || h >= s->n_q_heads)
+            return -1;
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < n_units; ++u)
+        unit_scores(s, q, k, units[3 * u], units[3 * u + 1], units[3 * u + 2],
+                    &head_cos[u], &head_dist[u]);
+    return 0;
+}
+
+/*
+ * All scores.  head_cos / head_dist: [B][L-1][Hq]; pair_cos / pair_dist: [B][L-1]
+ * (mean over the Hq query heads; each query head counts once).  Any output may
+ * be NULL except that the head arrays are always computed internally.
+ */
+int krul_oracle_pair_similarity(const oracle_shape_t *s, const void *q, const void *k,
+                                double *pair_cos, double *head_cos,
+                                double *pair_dist, double *head_dist)
+{
+    if (!shape_ok(s) || !q || !k)
+        return -1;
+    const int B = s->batch, NP = s->n_layers - 1, H = s->n_q_heads;
+    const int n_units = B * NP * H;
+    int32_t *units = (int32_t *)malloc(sizeof(int32_t) * 3 * (size_t)n_units);
+    double *hc = (double *)malloc(sizeof(double) * (size_t)n_units);
+    double *hd = (double *)malloc(sizeof(double) * (size_t)n_units);
+    int u = 0;
+    for (int b = 0; b < B; ++b)
+        for (int l = 0; l < NP; ++l)
+            for (int h = 0; h < H; ++h, ++u) {
+                units[3 * u] = b;
+                units[3 * u + 1] = l;
+                units[3 * u + 2] = h;
+            }
+    int rc = krul_oracle_units(s, q, k, n_units, units, hc, hd);
+    if (rc == 0) {
+        for (int bl = 0; bl < B * NP; ++bl) {
+            double cs = 0.0, ds = 0.0;
+            for (int h = 0; h < H; ++h) {
+                cs += hc[(size_t)bl * H + h];
+                ds += hd[(size_t)bl * H + h];
+            }
+            if (pair_cos) pair_cos[bl] = cs / H;
+            if (pair_dist) pair_dist[bl] = ds / H;
+        }
+        if (head_cos) memcpy(head_cos, hc, sizeof(double) * (size_t)n_units);
+        if (head_dist) memcpy(head_dist, hd, sizeof(double) * (size_t)n_units);
+    }
+    free(units);
+    free(hc);
+    free(hd);
+    return rc;
+}
+
+/*
+ * Alg. 1, second half (Sec. 4.2), for adjacent pairs.  pair_score[b][l] is the
+ * similarity of (l, l+1); larger means more alike, so "ascending distance" is
+ * descending score.  A pair is a candidate only if both its layers are eligible
+ * (eligible == NULL: all are).  Candidates are stably ordered by score (equal
+ * scores: lower layer index first) and scanned once; a pair is taken iff neither
+ * of its layers has been taken; the scan stops once n_select pairs are held.
+ * out_pairs[b][n_select] gets the lower layer index of each chosen pair in the
+ * order chosen, -1 beyond out_count[b].
+ */
+int krul_oracle_select_pairs(const double *pair_score, const uint8_t *eligible,
+                             int batch, int n_layers, int n_select,
+                             int32_t *out_pairs, int32_t *out_count)
+{
+    if (!pair_score || batch <= 0 || n_layers < 2 || n_select < 0 || !out_count ||
+        (n_select > 0 && !out_pairs))
+        return -1;
+    const int NP = n_layers - 1;
+    int *order = (int *)malloc(sizeof(int) * (size_t)NP);
+    uint8_t *shared = (uint8_t *)malloc((size_t)n_layers);
+    for (int b = 0; b < batch; ++b) {
+        const double *sc = pair_score + (size_t)b * NP;
+        const uint8_t *el = eligible ? eligible + (size_t)b * n_layers : NULL;
+        int n = 0;
+        for (int l = 0; l < NP; ++l)
+            if (!el || (el[l] && el[l + 1]))
+                order[n++] = l;
+        /* stable insertion sort, descending score */
+        for (int i = 1; i < n; ++i) {
+            int cur = order[i], j = i - 1;
+            while (j >= 0 && sc[order[j]] < sc[cur]) {
+                order[j + 1] = order[j];
+                --j;
+            }
+            order[j + 1] = cur;
+        }
+        memset(shared, 0, (size_t)n_layers);
+        int cnt = 0;
+        for (int i = 0; i < n && cnt < n_select; ++i) {
+            const int l = order[i];
+            if (shared[l] || shared[l + 1])
+                continue;
+            shared[l] = shared[l + 1] = 1;
+            out_pairs[(size_t)b * n_select + cnt++] = l;
+        }
+        out_count[b] = cnt;
+        for (int i = cnt; i < n_select; ++i)
+            out_pairs[(size_t)b * n_select + i] = -1;
+    }
+    free(order);
+    free(shared);
+    return 0;
+}
+
+/*
+ * Sec. 4.2, "Non-I-R Layer Extraction" / Alg. 1 first loop: for every layer, the
+ * attention mass that lands on the first tenth and on the last tenth of the
+ * history, averaged over all query heads and query rows.  Initial region: keys
+ * [0, floor(0.1*S)); recent region: keys [floor(0.9*S), S).  mass[b][l] is that
+ * mean; eligible[b][l] = (mass >= gamma), i.e. a layer whose mass stays below
+ * gamma is set aside as not input-insensitive.  Either output may be NULL.
+ */
+int krul_oracle_ir_mass(const oracle_shape_t *s, const void *q, const void *k,
+                        double gamma, double *mass, uint8_t *eligible)
+{
+    if (!shape_ok(s) || !q || !k)
+        return -1;
+    const int B = s->batch, L = s->n_layers, H = s->n_q_heads, S = s->n_hist, Tq = s->n_query;
+    const int n_init = (int)floor(0.1 * (double)S);
+    const int recent0 = (int)floor(0.9 * (double)S);
+    const int n_units = B * L * H;
+    double *unit_mass = (double *)malloc(sizeof(double) * (size_t)n_units);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < n_units; ++u) {
+        const int h = u % H, l = (u / H) % L, b = u / (H * L);
+        double *P = (double *)malloc(sizeof(double) * (size_t)Tq * S);
+        attention_weights(s, q, k, b, l, h, P);
+        double acc = 0.0;
+        for (int t = 0; t < Tq; ++t) {
+            const double *row = P + (size_t)t * S;
+            double m = 0.0;
+            for (int j = 0; j < n_init; ++j) m += row[j];
+            for (int j = recent0; j < S; ++j) m += row[j];
+            acc += m;
+        }
+        unit_mass[u] = acc / Tq;
+        free(P);
+    }
+    for (int bl = 0; bl < B * L; ++bl) {
+        double m = 0.0;
+        for (int h = 0; h < H; ++h) m += unit_mass[(size_t)bl * H + h];
+        m /= H;
+        if (mass) mass[bl] = m;
+        if (eligible) eligible[bl] = (uint8_t)(m >= gamma);
+    }
+    free(unit_mass);
+    return 0;
+}
+
+int krul_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
