@@ -1,0 +1,132 @@
+/*
+ * krul.h -- C ABI of the MI355X (gfx950) cross-layer attention-similarity library.
+ *
+ * The library implements the data-parallel core of Krul's compression-strategy
+ * search (arxiv 2507.08045): score how alike the attention patterns of adjacent
+ * layers are for a conversation (Sec. 4.2, Sec. 5, Sec. 7) and pick disjoint layer
+ * pairs under a budget (Alg. 1 second loop).
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers unless stated; the caller owns every
+ *     buffer.  The library allocates no device memory, keeps no state between
+ *     calls and is re-entrant.
+ *   - Work is only enqueued on the caller's stream (hipStream_t passed as void*,
+ *     NULL = the default stream); calls return without synchronising.
+ *   - The return value is a krul_status_t.  Nothing throws or aborts across the ABI.
+ *   - Tensors are dense, row-major, last index fastest.
+ */
+#ifndef KRUL_H
+#define KRUL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KRUL_OK = 0,
+    KRUL_EINVAL = -1,       /* null pointer, non-positive extent, bad head grouping, misalignment */
+    KRUL_EDTYPE = -2,       /* dtype is not a krul_dtype_t */
+    KRUL_EWORKSPACE = -3,   /* workspace missing, misaligned or shorter than the query says */
+    KRUL_ELAUNCH = -4,      /* the HIP runtime refused a launch */
+    KRUL_EUNSUPPORTED = -5  /* valid request with no kernel (head_dim, n_layers limits) */
+} krul_status_t;
+
+typedef enum { KRUL_F32 = 0, KRUL_BF16 = 1 } krul_dtype_t;
+
+/* flags of krul_shape_t */
+enum {
+    KRUL_FLAG_GENERIC_KERNEL = 1 << 8, /* testing aid: use the portable VALU kernel even where the
+                                          MFMA kernel applies (results agree to rounding) */
+    KRUL_FLAG_SINGLE_SPLIT = 1 << 9    /* do not split a row's keys over several workgroups
+                                          (less parallelism; exercises the multi-tile path) */
+};
+
+/*
+ * Problem statement.  Alg. 1 takes the model's attention weights for a prompt; here
+ * the forward pass is outside the library, so the attention weights are given by
+ * their factors: per layer l the queries Q_l and keys K_l, from which
+ * softmax(Q_l K_l^T * scale) of Sec. 2.1 is formed on the fly and never stored.
+ */
+typedef struct {
+    int32_t batch;        /* B   independent conversations                         */
+    int32_t n_layers;     /* L   transformer layers, >= 2                          */
+    int32_t n_q_heads;    /* Hq  query heads                                       */
+    int32_t n_kv_heads;   /* Hkv key heads, divides Hq; query head h reads kv head
+                                 h / (Hq/Hkv)                                      */
+    int32_t head_dim;     /* d   64 or 128 for bf16; multiple of 8, <= 256 for the
+                                 portable kernel                                   */
+    int32_t n_hist;       /* S   history keys per layer (every query row sees all) */
+    int32_t n_query;      /* Tq  query rows (tokens) per head                      */
+    int32_t dtype;        /* krul_dtype_t of q and k                               */
+    float   scale;        /* logit scale; 0 selects 1/sqrt(head_dim) (Sec. 2.1)    */
+    int32_t flags;        /* 0, or KRUL_FLAG_* bits                                */
+} krul_shape_t;
+
+/*
+ * Bytes of device workspace krul_pair_similarity needs for this
+ * shape (a multiple of 256).  Returns 0 if the shape is invalid or unsupported.
+ * Host-only: touches no GPU.
+ */
+size_t krul_pair_similarity_workspace(const krul_shape_t *shape);
+
+/*
+ * Token-wise cross-layer attention similarity (Sec. 5 and Sec. 7; distance of
+ * Alg. 1 / Sec. 4.2 for adjacent layers).  For every conversation b, adjacent pair
+ * l -> (l, l+1), query head h and query row t, with p = softmax(q_l K_l^T * scale)
+ * and r = softmax(q_{l+1} K_{l+1}^T * scale) over the S history keys:
+ *     cos  = <p, r> / (|p| |r|)            dist = |p - r|   (via p^2 + r^2 - 2pr, Sec. 7)
+ * aggregated token-wise: mean over t, then mean over the Hq query heads.
+ *
+ *   q           [B][L][Hq][Tq][d]   device, 16-byte aligned, dtype as in shape
+ *   k           [B][L][Hkv][S][d]   device, 16-byte aligned
+ *   pair_score  [B][L-1] float      device, required: mean cosine per pair
+ *   head_score  [B][L-1][Hq] float  device, may be NULL: mean cosine per pair and head
+ *   pair_dist   [B][L-1] float      device, may be NULL: mean Euclidean distance per pair
+ *   workspace   device, 256-byte aligned, at least krul_pair_similarity_workspace()
+ *               bytes; contents are scratch, undefined afterwards
+ *
+ * Results are deterministic (fixed reduction order).  Non-finite inputs give
+ * unspecified results.  Errors: KRUL_EINVAL, KRUL_EDTYPE, KRUL_EUNSUPPORTED,
+ * KRUL_EWORKSPACE, KRUL_ELAUNCH; on error nothing has been enqueued unless the
+ * code is KRUL_ELAUNCH.
+ */
+int krul_pair_similarity(const krul_shape_t *shape, const void *q, const void *k,
+                         float *pair_score, float *head_score, float *pair_dist,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Greedy disjoint pair selection (Alg. 1 second loop; Sec. 4.2).  Candidates are
+ * the adjacent pairs l -> (l, l+1) whose two layers are both eligible.  They are
+ * ordered by pair_score descending (= distance ascending), equal scores by lower l
+ * first, and scanned once: a pair is taken iff neither of its layers is already in
+ * a taken pair; the scan stops at n_select pairs.
+ *
+ *   pair_score [B][n_layers-1] float   device
+ *   eligible   [B][n_layers] uint8     device, or NULL = every layer eligible
+ *   out_pairs  [B][n_select] int32     device: lower layer index of each taken pair in
+ *                                      the order taken, -1 after out_count[b]
+ *   out_count  [B] int32               device: pairs taken (fewer than n_select when the
+ *                                      candidates run out; that is not an error)
+ * Limits: 2 <= n_layers <= 4096, 0 <= n_select <= n_layers/2.
+ */
+int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
+                      int32_t batch, int32_t n_layers, int32_t n_select,
+                      int32_t *out_pairs, int32_t *out_count, void *stream);
+
+/*
+ * Pairs to select for a compression ratio r_l: Alg. 1 stops once the shared-layer
+ * set holds N * r_l layers, two per pair, so ceil(N * r_l / 2), clamped to
+ * [0, N/2].  Host-only.
+ */
+int32_t krul_n_select_from_ratio(int32_t n_layers, float r_l);
+
+/* Static description of a status code.  Host-only. */
+const char *krul_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KRUL_H */

@@ -1,0 +1,159 @@
+"""ctypes binding of libkrul.so: argument marshalling only.
+
+Every step of the path (logits, online softmax statistics, cross term, row
+similarity, token-wise aggregation, pair selection) runs in the library's HIP
+kernels; this module only checks tensor types, allocates outputs and workspace with
+torch, and passes raw device pointers and the current HIP stream across the C ABI
+declared in include/krul.h.  There is no CPU fallback: if the library is missing
+or the tensors are not on a GPU, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libkrul.so")
+
+KRUL_OK, KRUL_EINVAL, KRUL_EDTYPE, KRUL_EWORKSPACE, KRUL_ELAUNCH, KRUL_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+KRUL_F32, KRUL_BF16 = 0, 1
+KRUL_FLAG_GENERIC_KERNEL = 1 << 8
+KRUL_FLAG_SINGLE_SPLIT = 1 << 9
+
+
+class KrulShape(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("n_hist", ctypes.c_int32),
+        ("n_query", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+        ("flags", ctypes.c_int32),
+    ]
+
+
+class KrulError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"libkrul: {strerror(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libkrul.so (built in-tree by build.py); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2507_08045_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        L.krul_pair_similarity_workspace.restype = sz
+        L.krul_pair_similarity_workspace.argtypes = [ctypes.POINTER(KrulShape)]
+        L.krul_pair_similarity.restype = ctypes.c_int
+        L.krul_pair_similarity.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.krul_select_pairs.restype = ctypes.c_int
+        L.krul_select_pairs.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+        L.krul_n_select_from_ratio.restype = i32
+        L.krul_n_select_from_ratio.argtypes = [i32, ctypes.c_float]
+        L.krul_strerror.restype = ctypes.c_char_p
+        L.krul_strerror.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().krul_strerror(int(status)).decode()
+
+
+def n_select_from_ratio(n_layers: int, r_l: float) -> int:
+    return int(lib().krul_n_select_from_ratio(int(n_layers), float(r_l)))
+
+
+def make_shape(q: torch.Tensor, k: torch.Tensor, scale: float = 0.0, flags: int = 0) -> KrulShape:
+    if q.dim() != 5 or k.dim() != 5:
+        raise ValueError("q must be [B,L,Hq,Tq,d] and k [B,L,Hkv,S,d]")
+    if q.dtype != k.dtype or q.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("q and k must both be float32 or both bfloat16")
+    B, L, Hq, Tq, d = q.shape
+    B2, L2, Hkv, S, d2 = k.shape
+    if (B, L, d) != (B2, L2, d2):
+        raise ValueError("q and k disagree on batch, layers or head_dim")
+    dt = KRUL_F32 if q.dtype == torch.float32 else KRUL_BF16
+    return KrulShape(B, L, Hq, Hkv, d, S, Tq, dt, float(scale), int(flags))
+
+
+def workspace_bytes(shape: KrulShape) -> int:
+    return int(lib().krul_pair_similarity_workspace(ctypes.byref(shape)))
+
+
+def _stream_ptr() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def pair_similarity(q: torch.Tensor, k: torch.Tensor, *, scale: float = 0.0, flags: int = 0,
+                    want_head_score: bool = True, want_pair_dist: bool = True,
+                    workspace: torch.Tensor | None = None, out: dict | None = None) -> dict:
+    """krul_pair_similarity on the current stream.  Returns device tensors
+    pair_score [B,L-1], head_score [B,L-1,Hq] (or None), pair_dist [B,L-1] (or None)."""
+    if not (q.is_cuda and k.is_cuda):
+        raise ValueError("q and k must be GPU tensors (this library has no CPU path)")
+    if not (q.is_contiguous() and k.is_contiguous()):
+        raise ValueError("q and k must be contiguous")
+    shp = make_shape(q, k, scale, flags)
+    need = workspace_bytes(shp)
+    if need == 0:
+        # let the library name the reason
+        rc = lib().krul_pair_similarity(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), None, None, None,
+                                        None, 0, None)
+        raise KrulError(rc if rc != 0 else KRUL_EINVAL)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    B, L, Hq = shp.batch, shp.n_layers, shp.n_q_heads
+    out = out or {}
+    ps = out.get("pair_score")
+    if ps is None:
+        ps = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
+    hs = out.get("head_score")
+    if hs is None and want_head_score:
+        hs = torch.empty((B, L - 1, Hq), dtype=torch.float32, device=q.device)
+    pd = out.get("pair_dist")
+    if pd is None and want_pair_dist:
+        pd = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
+    rc = lib().krul_pair_similarity(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), _dev_ptr(ps), _dev_ptr(hs),
+                                    _dev_ptr(pd), _dev_ptr(workspace), workspace.numel(),
+                                    ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace}
+
+
+def select_pairs(pair_score: torch.Tensor, n_select: int, eligible: torch.Tensor | None = None,
+                 out_pairs: torch.Tensor | None = None, out_count: torch.Tensor | None = None):
+    """krul_select_pairs on the current stream: (pairs [B,n_select] int32, count [B] int32)."""
+    if not pair_score.is_cuda or pair_score.dtype != torch.float32 or not pair_score.is_contiguous():
+        raise ValueError("pair_score must be a contiguous float32 GPU tensor")
+    if pair_score.dim() == 1:
+        pair_score = pair_score[None, :]
+    B, NP = pair_score.shape
+    L = NP + 1
+    if eligible is not None:
+        if not eligible.is_cuda or eligible.dtype != torch.uint8 or tuple(eligible.shape) != (B, L) \
+                or not eligible.is_contiguous():
+            raise ValueError("eligible must be a contiguous uint8 GPU tensor [B, n_layers]")
+    if out_pairs is None:
+        out_pairs = torch.empty((B, max(int(n_select), 0)), dtype=torch.int32, device=pair_score.device)
+    if out_count is None:
+        out_count = torch.empty((B,), dtype=torch.int32, device=pair_score.device)
+    rc = lib().krul_select_pairs(_dev_ptr(pair_score), _dev_ptr(eligible), B, L, int(n_select),
+                                 _dev_ptr(out_pairs), _dev_ptr(out_count), ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return out_pairs, out_count

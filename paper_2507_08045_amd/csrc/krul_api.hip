@@ -1,0 +1,190 @@
+// C ABI of libkrul: argument checks, kernel choice, launches.  See include/krul.h for
+// the contract of each entry point.
+#include <math.h>
+
+#include "krul_common.h"
+
+namespace krul {
+namespace {
+
+constexpr int kTargetWorkgroups = 512;   // two resident workgroups on each of 256 CUs
+constexpr size_t kAlign = 256;
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int check_shape(const krul_shape_t *s)
+{
+    if (!s) return KRUL_EINVAL;
+    if (s->dtype != KRUL_F32 && s->dtype != KRUL_BF16) return KRUL_EDTYPE;
+    if (s->batch <= 0 || s->n_layers < 2 || s->n_q_heads <= 0 || s->n_kv_heads <= 0 ||
+        s->head_dim <= 0 || s->n_hist <= 0 || s->n_query <= 0)
+        return KRUL_EINVAL;
+    if (s->n_q_heads % s->n_kv_heads != 0) return KRUL_EINVAL;
+    if (!(s->scale >= 0.f) || !isfinite(s->scale)) return KRUL_EINVAL;
+    if (s->flags & ~(KRUL_FLAG_GENERIC_KERNEL | KRUL_FLAG_SINGLE_SPLIT)) return KRUL_EINVAL;
+    if (s->head_dim % 8 != 0 || s->head_dim > 256) return KRUL_EUNSUPPORTED;
+    if (s->n_layers > 2048) return KRUL_EUNSUPPORTED;
+    return KRUL_OK;
+}
+
+}  // namespace
+
+int make_plan(const krul_shape_t *s, Plan *pl)
+{
+    const int rc = check_shape(s);
+    if (rc != KRUL_OK) return rc;
+    const long long B = s->batch, L = s->n_layers, Hq = s->n_q_heads, Hkv = s->n_kv_heads;
+    const long long S = s->n_hist, Tq = s->n_query, g = Hq / Hkv, Rk = g * Tq;
+    if (Rk > INT32_MAX || B * Hq * Tq > INT32_MAX) return KRUL_EUNSUPPORTED;
+
+    const float scale = s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->head_dim);
+    pl->c = scale * 1.4426950408889634f;
+    StateLayout &y = pl->lay;
+    y.n_layers = (int)L;
+    y.rows_per_unit = (int)Rk;
+
+    const bool mfma = s->dtype == KRUL_BF16 && (s->head_dim == 64 || s->head_dim == 128) &&
+                      !(s->flags & KRUL_FLAG_GENERIC_KERNEL);
+    long long n_wg, records, spill_records = 0;
+    if (mfma) {
+        int kt;
+        if (Rk <= 32) { y.variant = kMfmaSlim; y.wr = 1; y.wk = 4; y.rb = 1; kt = 1024; }
+        else if (Rk <= 64) { y.variant = kMfmaMid; y.wr = 1; y.wk = 4; y.rb = 2; kt = 512; }
+        else { y.variant = kMfmaWide; y.wr = 2; y.wk = 2; y.rb = 2; kt = 256; }
+        const long long r_wg = y.wr * y.rb * 32;
+        const long long nrt = (Rk + r_wg - 1) / r_wg;
+        const long long units = B * Hkv * nrt;
+        const long long tiles = (S + kt - 1) / kt;
+        long long want = (kTargetWorkgroups + units - 1) / units;
+        if (want < 1 || (s->flags & KRUL_FLAG_SINGLE_SPLIT)) want = 1;
+        long long nsplit = want < tiles ? want : tiles;
+        const long long tps = (tiles + nsplit - 1) / nsplit;
+        nsplit = (tiles + tps - 1) / tps;
+        y.n_row_tiles = (int)nrt;
+        y.n_split = (int)nsplit;
+        y.partials = (int)nsplit;
+        pl->keys_per_split = (int)(tps * kt);
+        n_wg = units * nsplit;
+        records = n_wg * L * r_wg;
+        if (tps > 1) spill_records = n_wg * L * 4 * y.rb * 64;
+    } else {
+        y.variant = kGeneric;
+        y.wr = y.wk = y.rb = 1;
+        y.n_row_tiles = 1;
+        const long long rows = B * Hq * Tq;
+        long long want = (2048 + rows - 1) / rows;
+        const long long max_split = (S + 255) / 256;
+        long long nsplit = want < max_split ? want : max_split;
+        if (nsplit < 1 || (s->flags & KRUL_FLAG_SINGLE_SPLIT)) nsplit = 1;
+        long long kps = ((S + nsplit - 1) / nsplit + 63) / 64 * 64;
+        nsplit = (S + kps - 1) / kps;
+        y.n_split = (int)nsplit;
+        y.partials = (int)nsplit;
+        pl->keys_per_split = (int)kps;
+        n_wg = rows * nsplit;
+        records = n_wg * L;
+    }
+    if (n_wg > INT32_MAX) return KRUL_EUNSUPPORTED;
+    pl->n_workgroups = (int)n_wg;
+    pl->state_bytes = round_up((size_t)records * sizeof(float4), kAlign);
+    pl->spill_bytes = round_up((size_t)spill_records * sizeof(float4), kAlign);
+    const size_t head_bytes = round_up((size_t)(B * (L - 1) * Hq) * sizeof(float), kAlign);
+    pl->spill_off = pl->state_bytes;
+    pl->head_cos_off = pl->spill_off + pl->spill_bytes;
+    pl->head_dist_off = pl->head_cos_off + head_bytes;
+    pl->total_bytes = pl->head_dist_off + head_bytes;
+    return KRUL_OK;
+}
+
+}  // namespace krul
+
+using namespace krul;
+
+extern "C" {
+
+size_t krul_pair_similarity_workspace(const krul_shape_t *shape)
+{
+    Plan pl;
+    if (make_plan(shape, &pl) != KRUL_OK) return 0;
+    return pl.total_bytes;
+}
+
+int krul_pair_similarity(const krul_shape_t *shape, const void *q, const void *k,
+                         float *pair_score, float *head_score, float *pair_dist,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    const int rc = make_plan(shape, &pl);
+    if (rc != KRUL_OK) return rc;
+    if (!q || !k || !pair_score) return KRUL_EINVAL;
+    if (((uintptr_t)q | (uintptr_t)k) & 15) return KRUL_EINVAL;
+    if (((uintptr_t)pair_score | (uintptr_t)head_score | (uintptr_t)pair_dist) & 3) return KRUL_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & (kAlign - 1)) || workspace_bytes < pl.total_bytes)
+        return KRUL_EWORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    SimParams p;
+    p.q = q;
+    p.k = k;
+    p.state = reinterpret_cast<float4 *>(ws);
+    p.spill = reinterpret_cast<float4 *>(ws + pl.spill_off);
+    p.B = shape->batch;
+    p.L = shape->n_layers;
+    p.Hq = shape->n_q_heads;
+    p.Hkv = shape->n_kv_heads;
+    p.g = p.Hq / p.Hkv;
+    p.d = shape->head_dim;
+    p.S = shape->n_hist;
+    p.Tq = shape->n_query;
+    p.keys_per_split = pl.keys_per_split;
+    p.c = pl.c;
+    p.lay = pl.lay;
+
+    hipError_t e = pl.lay.variant == kGeneric
+                       ? launch_sim_generic(p, shape->dtype, pl.n_workgroups, st)
+                       : launch_sim_mfma(p, pl.n_workgroups, st);
+    if (e != hipSuccess) return KRUL_ELAUNCH;
+    float *head_cos = head_score ? head_score : reinterpret_cast<float *>(ws + pl.head_cos_off);
+    float *head_dist = reinterpret_cast<float *>(ws + pl.head_dist_off);
+    e = launch_finalize(pl.lay, p.state, p.B, p.L, p.Hq, p.Hkv, p.Tq, head_cos, head_dist,
+                        pair_score, pair_dist, st);
+    return e == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
+}
+
+int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
+                      int32_t batch, int32_t n_layers, int32_t n_select,
+                      int32_t *out_pairs, int32_t *out_count, void *stream)
+{
+    if (!pair_score || !out_count || batch <= 0 || n_layers < 2 || n_select < 0 ||
+        n_select > n_layers / 2 || (n_select > 0 && !out_pairs))
+        return KRUL_EINVAL;
+    if (((uintptr_t)pair_score | (uintptr_t)out_pairs | (uintptr_t)out_count) & 3) return KRUL_EINVAL;
+    if (n_layers > 4096) return KRUL_EUNSUPPORTED;
+    const hipError_t e = launch_select(pair_score, eligible, batch, n_layers, n_select, out_pairs,
+                                       out_count, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
+}
+
+int32_t krul_n_select_from_ratio(int32_t n_layers, float r_l)
+{
+    if (n_layers < 2 || !(r_l > 0.f)) return 0;
+    const double want = ceil((double)n_layers * (double)r_l / 2.0 - 1e-9);
+    const int32_t cap = n_layers / 2;
+    return want > cap ? cap : (int32_t)want;
+}
+
+const char *krul_strerror(int status)
+{
+    switch (status) {
+    case KRUL_OK: return "ok";
+    case KRUL_EINVAL: return "invalid argument";
+    case KRUL_EDTYPE: return "unknown dtype";
+    case KRUL_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case KRUL_ELAUNCH: return "kernel launch failed";
+    case KRUL_EUNSUPPORTED: return "no kernel for this shape";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,100 @@
+// Internal declarations shared by the translation units of libkrul (not installed).
+//
+// Data flow of krul_pair_similarity (Sec. 5 / Sec. 7 of the paper: similarity is
+// accumulated token-wise, attention weights are never kept):
+//   1. a similarity kernel walks the history keys tile by tile and, inside a tile,
+//      the layers in order.  For each (row, layer) it maintains the online-softmax
+//      statistics  m (reference exponent), Z = sum e, N2 = sum e^2  with
+//      e = 2^(x - m), x = logit * scale * log2(e); for each adjacent pair it
+//      maintains the cross term  C = sum e_l * e_{l+1}  (the "-2ab" term of the
+//      a^2 + b^2 - 2ab expansion in Sec. 7).  A row's keys may be spread over several
+//      independent "partials" (lanes, waves, key splits).  Partials inside a
+//      workgroup are merged there; each key split writes one record per (row,
+//      layer), float4 (m, Z, N2, C(l-1,l)), to the state area of the workspace.
+//   2. the finalize kernel merges a row's partials (rescaling to the common
+//      reference exponent), forms cos = C / sqrt(N2_l N2_{l+1}) and
+//      dist^2 = N2_l/Z_l^2 + N2_{l+1}/Z_{l+1}^2 - 2C/(Z_l Z_{l+1}), and averages over
+//      the query rows of a head in a fixed order;
+//   3. the pair kernel averages over heads.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "krul.h"
+
+namespace krul {
+
+// Reference exponent of a partial that has seen no key yet: finite, so that
+// differences of exponents never give inf - inf.
+constexpr float kMInit = -1.0e30f;
+
+enum Variant : int {
+    kGeneric = 0,   // portable VALU kernel: one wave per (row, key split)
+    kMfmaWide = 1,  // bf16 MFMA, 128 rows x 256 keys per workgroup tile (2x2 waves)
+    kMfmaMid = 2,   // bf16 MFMA,  64 rows x 512 keys per workgroup tile (1x4 waves)
+    kMfmaSlim = 3,  // bf16 MFMA,  32 rows x 1024 keys per workgroup tile (1x4 waves)
+};
+
+// How the state records of one launch are laid out; used by the producer kernels
+// and by the finalize kernel.
+struct StateLayout {
+    int variant;
+    int n_layers;
+    int rows_per_unit;   // Rk = (Hq/Hkv) * Tq rows share one kv head
+    int n_split;         // key splits (workgroups along the keys)
+    int n_row_tiles;     // workgroups along the rows of a unit (MFMA variants)
+    int wr, wk, rb;      // wave grid and 32-row blocks per wave (MFMA variants)
+    int partials;        // records per (row, layer)
+};
+
+struct Plan {
+    StateLayout lay;
+    int keys_per_split;  // multiple of the key tile for MFMA variants
+    int n_workgroups;
+    float c;             // scale * log2(e)
+    size_t state_bytes;  // merged partial records (float4), read by the finalize kernel
+    size_t spill_bytes;  // per-lane running records of multi-tile splits (MFMA variants)
+    size_t spill_off, head_cos_off, head_dist_off, total_bytes;
+};
+
+// Host: choose kernel and decomposition for a validated shape.  Returns a
+// krul_status_t.
+int make_plan(const krul_shape_t *s, Plan *plan);
+
+struct SimParams {
+    const void *q;
+    const void *k;
+    float4 *state;   // partial records, indexed by state_index()
+    float4 *spill;   // MFMA variants: per-lane running records between key tiles
+    int B, L, Hq, Hkv, g, d, S, Tq;
+    int keys_per_split;
+    float c;
+    StateLayout lay;
+};
+
+// Launchers (each returns hipError_t of the launch).
+hipError_t launch_sim_generic(const SimParams &p, int dtype, int n_workgroups, hipStream_t st);
+hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st);
+hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, int L, int Hq, int Hkv,
+                           int Tq, float *head_cos, float *head_dist, float *pair_cos,
+                           float *pair_dist, hipStream_t st);
+hipError_t launch_select(const float *pair_score, const uint8_t *eligible, int batch, int n_layers,
+                         int n_select, int32_t *out_pairs, int32_t *out_count, hipStream_t st);
+
+// Index (in float4 records) of the record of partial p of row r of unit u
+// (u = b * Hkv + kv head; r = head-in-group * Tq + t) for layer l.
+__host__ __device__ inline size_t state_index(const StateLayout &y, int u, int r, int p, int l)
+{
+    if (y.variant == kGeneric) {
+        const size_t grow = (size_t)u * y.rows_per_unit + r;
+        return (grow * y.n_split + p) * y.n_layers + l;
+    }
+    // MFMA variants: one record per (workgroup, layer, row); partial p = key split
+    const int r_wg = y.wr * y.rb * 32;
+    const int rt = r / r_wg, rr = r % r_wg;
+    const size_t wg = ((size_t)u * y.n_split + p) * y.n_row_tiles + rt;
+    return (wg * y.n_layers + l) * r_wg + rr;
+}
+
+}  // namespace krul
