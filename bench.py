@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the cross-layer attention-similarity path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input already
+resident in HBM: krul_pair_similarity (logits, online softmax sums, cross term, row
+similarity, token-wise aggregation) followed by krul_select_pairs, on one stream.
+Prints ONE JSON line.  Metric: layer-pair similarity throughput in Gscore-elems/s,
+score-elems = B*(L-1)*Hq*Tq*S (one per pair of attention probabilities compared).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def algorithmic_bytes(w) -> int:
+    """Every K and Q element once, plus the score outputs."""
+    e = 4 if w.dtype == "f32" else 2
+    return w.B * w.L * w.d * e * (w.Hkv * w.S + w.Hq * w.Tq) + 4 * w.B * (w.L - 1) * (w.Hq + 1)
+
+
+def algorithmic_flops(w) -> int:
+    """Each layer's logits once: 2*d flops per logit."""
+    return 2 * w.d * w.B * w.L * w.Hq * w.Tq * w.S
+
+
+def cpu_baseline(w, seconds_target=15.0):
+    """The fp64 oracle, as it stands, on a bounded sample of (b, pair, head) units."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    n_all = w.B * (w.L - 1) * w.Hq
+    rng = np.random.default_rng(12345)
+    all_units = [(b, l, h) for b in range(w.B) for l in range(w.L - 1) for h in range(w.Hq)]
+    threads = oracle.num_threads()
+    # calibrate on one unit per thread, then size the sample for ~seconds_target
+    probe = [all_units[i] for i in rng.choice(n_all, size=min(threads, n_all), replace=False)]
+    t0 = time.perf_counter()
+    oracle.unit_scores(w.q, w.k, probe)
+    t_probe = time.perf_counter() - t0
+    n = int(min(n_all, max(threads, threads * (seconds_target / max(t_probe, 1e-3)))))
+    n = max(threads, n // threads * threads)
+    n = min(n, n_all)
+    sample = [all_units[i] for i in rng.choice(n_all, size=n, replace=False)]
+    t0 = time.perf_counter()
+    oracle.unit_scores(w.q, w.k, sample)
+    dt = time.perf_counter() - t0
+    elems = n * w.Tq * w.S
+    return {
+        "value": elems / dt / 1e9, "unit": "Gscore-elems/s", "cores": threads, "kind": "oracle",
+        "sample": f"{n} of {n_all} (conversation, pair, head) units of {w.name}, all rows and keys, "
+                  f"{dt:.1f} s wall",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--flags", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only; --gpus above 1 is not supported "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2507_08045_amd as kr
+    from paper_2507_08045_amd import hipevents
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    w = workloads.config(args.config)
+    if w.dtype == "f32":
+        q, k = torch.from_numpy(w.q).cuda(), torch.from_numpy(w.k).cuda()
+    else:
+        q = torch.from_numpy(w.q.view(np.int16)).cuda().view(torch.bfloat16)
+        k = torch.from_numpy(w.k.view(np.int16)).cuda().view(torch.bfloat16)
+
+    shp = kr.make_shape(q, k, 0.0, args.flags)
+    ws = torch.empty(kr.workspace_bytes(shp), dtype=torch.uint8, device="cuda")
+    out = {
+        "pair_score": torch.empty((w.B, w.L - 1), dtype=torch.float32, device="cuda"),
+        "head_score": torch.empty((w.B, w.L - 1, w.Hq), dtype=torch.float32, device="cuda"),
+        "pair_dist": torch.empty((w.B, w.L - 1), dtype=torch.float32, device="cuda"),
+    }
+    pairs = torch.empty((w.B, w.n_select), dtype=torch.int32, device="cuda")
+    count = torch.empty((w.B,), dtype=torch.int32, device="cuda")
+    K = args.steps
+    evs = [(hipevents.create(), hipevents.create()) for _ in range(K)]
+
+    def step(ev=None):
+        kr.pair_similarity(q, k, flags=args.flags, workspace=ws, out=out, events=ev)
+        kr.select_pairs(out["pair_score"], w.n_select, out_pairs=pairs, out_count=count)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(evs[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    kern_ms = [hipevents.elapsed_ms(a, b) for a, b in evs]
+    for a, b in evs:
+        hipevents.destroy(a)
+        hipevents.destroy(b)
+    kern_s = float(np.mean(kern_ms)) * 1e-3
+    ms_per_step = dt / K * 1e3
+    value = w.score_elems / (dt / K) / 1e9
+
+    bytes_alg, flops_alg = algorithmic_bytes(w), algorithmic_flops(w)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    hbm_gbs = bytes_alg / kern_s / 1e9
+    mfma_tflops = flops_alg / kern_s / 1e12
+    res = {
+        "metric": "layer-pair similarity throughput", "value": value, "unit": "Gscore-elems/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} L={w.L} Hq/Hkv={w.Hq}/{w.Hkv} d={w.d} S={w.S} Tq={w.Tq} "
+                               f"{w.dtype}, select {w.n_select} pairs", "score_elems": w.score_elems},
+        "roofline": {"bound": "hbm", "achieved": hbm_gbs, "peak": 8000.0, "unit": "GB/s",
+                     "frac": hbm_gbs / 8000.0, "traffic": traffic,
+                     "kernel": "sim_mfma_kernel" if w.dtype == "bf16" and not (args.flags & 256) else "sim_generic_kernel",
+                     "kernel_us": kern_s * 1e6, "algorithmic_bytes": bytes_alg},
+        "roofline_mfma": {"bound": "mfma", "achieved": mfma_tflops, "peak": 2500.0, "unit": "TFLOP/s",
+                          "frac": mfma_tflops / 2500.0, "algorithmic_flops": flops_alg},
+        "selected_pairs": pairs.cpu().tolist()[0],
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -98,6 +98,18 @@ int krul_pair_similarity(const krul_shape_t *shape, const void *q, const void *k
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * krul_pair_similarity with two caller-created HIP events (hipEvent_t passed as void*,
+ * either may be NULL) recorded on the stream immediately before and after the
+ * similarity kernel -- the kernel that forms the logits and the softmax sums and
+ * dominates the run time -- so that a harness can time that one kernel inside its own
+ * timed region.  Everything else is as for krul_pair_similarity.
+ */
+int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const void *k,
+                               float *pair_score, float *head_score, float *pair_dist,
+                               void *workspace, size_t workspace_bytes, void *stream,
+                               void *event_begin, void *event_end);
+
+/*
  * Greedy disjoint pair selection (Alg. 1 second loop; Sec. 4.2).  Candidates are
  * the adjacent pairs l -> (l, l+1) whose two layers are both eligible.  They are
  * ordered by pair_score descending (= distance ascending), equal scores by lower l

@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_workspace.argtypes = [ctypes.POINTER(KrulShape)]
         L.krul_pair_similarity.restype = ctypes.c_int
         L.krul_pair_similarity.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.krul_pair_similarity_timed.restype = ctypes.c_int
+        L.krul_pair_similarity_timed.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
         L.krul_select_pairs.restype = ctypes.c_int
         L.krul_select_pairs.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
         L.krul_n_select_from_ratio.restype = i32
@@ -100,7 +102,8 @@ def _dev_ptr(t):
 
 def pair_similarity(q: torch.Tensor, k: torch.Tensor, *, scale: float = 0.0, flags: int = 0,
                     want_head_score: bool = True, want_pair_dist: bool = True,
-                    workspace: torch.Tensor | None = None, out: dict | None = None) -> dict:
+                    workspace: torch.Tensor | None = None, out: dict | None = None,
+                    events: tuple | None = None) -> dict:
     """krul_pair_similarity on the current stream.  Returns device tensors
     pair_score [B,L-1], head_score [B,L-1,Hq] (or None), pair_dist [B,L-1] (or None)."""
     if not (q.is_cuda and k.is_cuda):
@@ -127,9 +130,15 @@ def pair_similarity(q: torch.Tensor, k: torch.Tensor, *, scale: float = 0.0, fla
     pd = out.get("pair_dist")
     if pd is None and want_pair_dist:
         pd = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
-    rc = lib().krul_pair_similarity(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), _dev_ptr(ps), _dev_ptr(hs),
-                                    _dev_ptr(pd), _dev_ptr(workspace), workspace.numel(),
-                                    ctypes.c_void_p(_stream_ptr()))
+    if events is not None:   # (hipEvent_t, hipEvent_t) raw handles around the similarity kernel
+        rc = lib().krul_pair_similarity_timed(
+            ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), _dev_ptr(ps), _dev_ptr(hs), _dev_ptr(pd),
+            _dev_ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr()),
+            ctypes.c_void_p(events[0]), ctypes.c_void_p(events[1]))
+    else:
+        rc = lib().krul_pair_similarity(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), _dev_ptr(ps), _dev_ptr(hs),
+                                        _dev_ptr(pd), _dev_ptr(workspace), workspace.numel(),
+                                        ctypes.c_void_p(_stream_ptr()))
     if rc != KRUL_OK:
         raise KrulError(rc)
     return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace}

@@ -113,6 +113,15 @@ int krul_pair_similarity(const krul_shape_t *shape, const void *q, const void *k
                          float *pair_score, float *head_score, float *pair_dist,
                          void *workspace, size_t workspace_bytes, void *stream)
 {
+    return krul_pair_similarity_timed(shape, q, k, pair_score, head_score, pair_dist, workspace,
+                                      workspace_bytes, stream, nullptr, nullptr);
+}
+
+int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const void *k,
+                               float *pair_score, float *head_score, float *pair_dist,
+                               void *workspace, size_t workspace_bytes, void *stream,
+                               void *event_begin, void *event_end)
+{
     Plan pl;
     const int rc = make_plan(shape, &pl);
     if (rc != KRUL_OK) return rc;
@@ -141,10 +150,14 @@ int krul_pair_similarity(const krul_shape_t *shape, const void *q, const void *k
     p.c = pl.c;
     p.lay = pl.lay;
 
+    if (event_begin && hipEventRecord(static_cast<hipEvent_t>(event_begin), st) != hipSuccess)
+        return KRUL_ELAUNCH;
     hipError_t e = pl.lay.variant == kGeneric
                        ? launch_sim_generic(p, shape->dtype, pl.n_workgroups, st)
                        : launch_sim_mfma(p, pl.n_workgroups, st);
     if (e != hipSuccess) return KRUL_ELAUNCH;
+    if (event_end && hipEventRecord(static_cast<hipEvent_t>(event_end), st) != hipSuccess)
+        return KRUL_ELAUNCH;
     float *head_cos = head_score ? head_score : reinterpret_cast<float *>(ws + pl.head_cos_off);
     float *head_dist = reinterpret_cast<float *>(ws + pl.head_dist_off);
     e = launch_finalize(pl.lay, p.state, p.B, p.L, p.Hq, p.Hkv, p.Tq, head_cos, head_dist,
