@@ -310,14 +310,14 @@ hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
     const bool d128 = p.d == 128;
     switch (p.lay.variant) {
     case kMfmaWide:
-        return d128 ? launch_cfg<Cfg<128, 2, 2, 2, 4>>(p, n_workgroups, st)
-                    : launch_cfg<Cfg<64, 2, 2, 2, 4>>(p, n_workgroups, st);
+        return d128 ? launch_cfg<Cfg<128, 2, 2, 2, 2>>(p, n_workgroups, st)
+                    : launch_cfg<Cfg<64, 2, 2, 2, 2>>(p, n_workgroups, st);
     case kMfmaMid:
-        return d128 ? launch_cfg<Cfg<128, 1, 4, 2, 4>>(p, n_workgroups, st)
-                    : launch_cfg<Cfg<64, 1, 4, 2, 4>>(p, n_workgroups, st);
+        return d128 ? launch_cfg<Cfg<128, 1, 4, 2, 2>>(p, n_workgroups, st)
+                    : launch_cfg<Cfg<64, 1, 4, 2, 2>>(p, n_workgroups, st);
     case kMfmaSlim:
-        return d128 ? launch_cfg<Cfg<128, 1, 4, 1, 8>>(p, n_workgroups, st)
-                    : launch_cfg<Cfg<64, 1, 4, 1, 8>>(p, n_workgroups, st);
+        return d128 ? launch_cfg<Cfg<128, 1, 4, 1, 4>>(p, n_workgroups, st)
+                    : launch_cfg<Cfg<64, 1, 4, 1, 4>>(p, n_workgroups, st);
     default:
         return hipErrorInvalidValue;
     }
