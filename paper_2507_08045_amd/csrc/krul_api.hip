@@ -50,7 +50,7 @@ int make_plan(const krul_shape_t *s, Plan *pl)
         int kt;
         if (Rk <= 32) { y.variant = kMfmaSlim; y.wr = 1; y.wk = 4; y.rb = 1; kt = 512; }
         else if (Rk <= 64) { y.variant = kMfmaMid; y.wr = 1; y.wk = 4; y.rb = 2; kt = 256; }
-        else { y.variant = kMfmaWide; y.wr = 2; y.wk = 2; y.rb = 2; kt = 128; }
+        else { y.variant = kMfmaWide; y.wr = 4; y.wk = 1; y.rb = 1; kt = 128; }
         const long long r_wg = y.wr * y.rb * 32;
         const long long nrt = (Rk + r_wg - 1) / r_wg;
         const long long units = B * Hkv * nrt;

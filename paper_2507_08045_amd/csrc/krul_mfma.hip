@@ -7,14 +7,21 @@
 // exactly once and the previous layer's exponentials of the same keys are still in
 // registers when the cross term (the "ab" of Sec. 7's a^2 + b^2 - 2ab) is taken.
 //
-// Per layer step the K tile arrives in chunks of CH = 32*WK keys: global -> registers
-// -> LDS (row stride padded by 16 bytes, which spreads 16 consecutive rows over all
-// banks for 16-byte reads), double buffered, one barrier per chunk.  Each wave takes
-// one 32-key block of the chunk and RB blocks of 32 query rows:
+// K stream.  Per layer step the K tile arrives in NC chunks of CH keys.  Chunks are
+// copied HBM -> LDS by global_load_lds_dwordx4 (no register staging) into a ring of
+// NBUF slots, NBUF-1 chunks ahead of the compute; one s_waitcnt + s_barrier per chunk
+// publishes a slot.  Every slot is its own LDS object and every use names its slot
+// statically, so the compiler can tell a copy in flight from the slot being read and
+// adds no waits of its own.  Inside a slot 16-byte pieces are XOR-swizzled by row so
+// that the 16-byte MFMA operand reads of 16 consecutive rows hit 16 different bank
+// groups (the swizzle is applied on the global side: each lane fetches the piece that
+// belongs in its LDS position).
+//
+// Math.  Per chunk each wave takes KBW blocks of 32 keys and RB blocks of 32 query rows:
 //     S^T (32 keys x 32 rows) = K_blk (32 x d) * Q_blk^T (d x 32)
-// with v_mfma_f32_32x32x16_bf16, A = keys (from LDS), B = query rows (held in
-// registers for the whole layer step).  In the result every lane owns ONE query row
-// (column lane%32) and 16 keys, so all softmax reductions are lane-local: no
+// with v_mfma_f32_32x32x16_bf16, A = keys (from LDS), B = query rows (registers, loaded
+// once per layer step straight from global memory).  In the result every lane owns ONE
+// query row (column lane%32) and 16 keys, so all softmax reductions are lane-local: no
 // cross-lane traffic in the loop.  Lanes l and l+32 and the WK waves along the keys
 // are independent partials of a row, merged once after the last tile.
 //
@@ -33,22 +40,30 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr float kLazy = 16.0f;
 
-template <int D_, int WR_, int WK_, int RB_, int NKB_>
+template <int D_, int WR_, int WK_, int RB_, int KBW_, int NC_, int NBUF_>
 struct Cfg {
-    static constexpr int D = D_, WR = WR_, WK = WK_, RB = RB_, NKB = NKB_;
+    static constexpr int D = D_, WR = WR_, WK = WK_, RB = RB_, KBW = KBW_, NC = NC_, NBUF = NBUF_;
     static constexpr int NW = WR * WK;
     static constexpr int THREADS = NW * 64;
-    static constexpr int R_WG = WR * RB * 32;
-    static constexpr int CH = WK * 32;             // keys per chunk
-    static constexpr int KT = CH * NKB;            // keys per tile
+    static constexpr int R_WG = WR * RB * 32;      // query rows per workgroup
+    static constexpr int CH = WK * KBW * 32;       // keys per chunk
+    static constexpr int KT = CH * NC;             // keys per tile
+    static constexpr int NBLK = NC * KBW;          // 32-key blocks per wave per tile
     static constexpr int KS = D / 16;              // MFMA k-steps per 32x32 block
-    static constexpr int ROWB = D * 2 + 16;        // LDS row stride, bytes
-    static constexpr int CHUNK_BYTES = CH * ROWB;
-    static constexpr int PIECES_PER_ROW = D / 8;   // 16-byte pieces per key row
-    static constexpr int NLD = CH * PIECES_PER_ROW / THREADS;  // pieces per thread per chunk
+    static constexpr int PPR = D / 8;              // 16-byte pieces per key row
+    static constexpr int SLOT_BYTES = CH * D * 2;
+    static constexpr int NLD = CH * PPR / THREADS; // direct-to-LDS loads per thread per chunk
+    static constexpr int PF = NBUF - 1;            // chunks in flight ahead of the compute
     static_assert(NW == 4, "four waves per workgroup");
-    static_assert(CH * PIECES_PER_ROW % THREADS == 0, "chunk must split evenly over threads");
+    static_assert(CH * PPR % THREADS == 0, "chunk must split evenly over threads");
+    static_assert(NBUF == NC || NBUF == 2 * NC, "ring must be one or two tiles deep");
+    static_assert(NBUF >= 2 && NBUF <= 4, "two to four ring slots");
+    static_assert(D == 64 || D == 128, "head_dim 64 or 128");
 };
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8]).
+constexpr int wait_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+constexpr int kWaitLgkm0 = 0xC07F;
 
 // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
 // logical ids so that workgroups sharing K (neighbouring row tiles) share an L2.
@@ -58,12 +73,31 @@ __device__ inline int xcd_remap(int bid, int n)
     return x * q + min(x, rem) + (bid >> 3);
 }
 
+// Row-dependent XOR applied to the piece index inside an LDS slot.
+template <int D>
+__device__ inline int swz(int row)
+{
+    return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+
 template <class C>
 __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 {
-    constexpr int D = C::D, WK = C::WK, RB = C::RB, NKB = C::NKB, KS = C::KS, NLD = C::NLD;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][C::CHUNK_BYTES];
+    constexpr int D = C::D, WK = C::WK, RB = C::RB, KBW = C::KBW, NC = C::NC, KS = C::KS;
+    constexpr int NLD = C::NLD, NBUF = C::NBUF, PF = C::PF, PPR = C::PPR, NBLK = C::NBLK;
+    __shared__ __attribute__((aligned(1024))) unsigned char ring0[C::SLOT_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char ring1[C::SLOT_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char ring2[NBUF > 2 ? C::SLOT_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char ring3[NBUF > 3 ? C::SLOT_BYTES : 16];
     __shared__ float red[C::NW][RB][4][32];
+    auto slot_ptr = [&](int i) __attribute__((always_inline)) -> unsigned char * {
+        switch (i) {   // i is a constant at every call site once the loops are unrolled
+        case 0: return ring0;
+        case 1: return ring1;
+        case 2: return ring2;
+        default: return ring3;
+        }
+    };
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave / WK, wk = wave % WK, half = lane >> 5, l32 = lane & 31;
@@ -77,34 +111,42 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     const int key_begin = sp * p.keys_per_split;
     const int key_end = min(S, key_begin + p.keys_per_split);
     const int ntiles = (key_end - key_begin + C::KT - 1) / C::KT;
-    const int nchunks = ntiles * L * NKB;
+    const int nchunks = ntiles * L * NC;
 
     // ---- query rows of this lane (clamped; rows past the unit are never read back)
     const uint16_t *Qg = static_cast<const uint16_t *>(p.q);
     const uint16_t *Kg = static_cast<const uint16_t *>(p.k);
     const size_t q_layer_stride = (size_t)p.Hq * p.Tq * D;
     const size_t k_layer_stride = (size_t)p.Hkv * S * D;
-    const uint16_t *qptr[RB];
+    const uint16_t *qbase = Qg + ((size_t)b * L * p.Hq * p.Tq + (size_t)kvh * Rk) * D;
+    int qoff[RB];   // element offset of this lane's query row inside a layer
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int r = min(rt * C::R_WG + (wr * RB + rb) * 32 + l32, Rk - 1);
-        qptr[rb] = Qg + ((size_t)b * L * p.Hq * p.Tq + (size_t)kvh * Rk + r) * D + half * 8;
-    }
+    for (int rb = 0; rb < RB; ++rb)
+        qoff[rb] = min(rt * C::R_WG + (wr * RB + rb) * 32 + l32, Rk - 1) * D + half * 8;
     const uint16_t *kbase = Kg + ((size_t)b * L * p.Hkv + kvh) * (size_t)S * D;
 
-    // ---- chunk staging: piece i = tid + j*THREADS -> key i / (D/8), 16-byte piece i % (D/8)
-    uint4 stg[NLD];
-    int pf_tile = 0, pf_l = 0, pf_c = 0;   // position of the next chunk to fetch
-    auto fetch_chunk = [&]() {
+    // ---- K ring: wave-instruction j of this wave fills granules [(wave*NLD+j)*64, +64)
+    // of a slot; the lane at granule g = row*PPR + pc fetches piece pc ^ swz(row) of row.
+    int ld_row[NLD], ld_col[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int g = (wave * NLD + j) * 64 + lane;
+        ld_row[j] = g / PPR;
+        ld_col[j] = ((g % PPR) ^ swz<D>(g / PPR)) * 8;
+    }
+    int pf_tile = 0, pf_l = 0, pf_c = 0;   // next chunk to fetch
+    auto issue_chunk = [&](int slot) __attribute__((always_inline)) {
+        unsigned char *dst = slot_ptr(slot);
         const int key0 = key_begin + pf_tile * C::KT + pf_c * C::CH;
         const uint16_t *src = kbase + (size_t)pf_l * k_layer_stride;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-            const int i = tid + j * C::THREADS;
-            const int key = min(key0 + i / C::PIECES_PER_ROW, S - 1);
-            stg[j] = *reinterpret_cast<const uint4 *>(src + (size_t)key * D + (i % C::PIECES_PER_ROW) * 8);
+            const int key = min(key0 + ld_row[j], S - 1);
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(src + (size_t)key * D + ld_col[j]),
+                (__attribute__((address_space(3))) void *)(dst + (wave * NLD + j) * 1024), 16, 0, 0);
         }
-        if (++pf_c == NKB) {
+        if (++pf_c == NC) {
             pf_c = 0;
             if (++pf_l == L) {
                 pf_l = 0;
@@ -112,55 +154,59 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
             }
         }
     };
-    auto stage_chunk = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < NLD; ++j) {
-            const int i = tid + j * C::THREADS;
-            *reinterpret_cast<uint4 *>(&lds[buf][(i / C::PIECES_PER_ROW) * C::ROWB + (i % C::PIECES_PER_ROW) * 16]) = stg[j];
-        }
-    };
 
     bf16x8 qf[RB][KS];
-    auto load_q = [&](int l) {
+    auto load_q = [&](int l) __attribute__((always_inline)) {
+        const uint16_t *ql = qbase + (size_t)l * q_layer_stride;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                qf[rb][ks] = *reinterpret_cast<const bf16x8 *>(qptr[rb] + (size_t)l * q_layer_stride + ks * 16);
+                qf[rb][ks] = *reinterpret_cast<const bf16x8 *>(ql + qoff[rb] + ks * 16);
     };
 
-    // per-lane spill records (only used when the split spans several tiles)
+    // per-lane running records between key tiles (only when the split spans several tiles)
     float4 *spill = p.spill;
     auto spill_index = [&](int l, int rb) -> size_t {
         return (((((size_t)wg * L + l) * C::NW + wave) * RB + rb) << 6) + lane;
     };
 
-    float e[RB][NKB][16];
+    float e[RB][NBLK][16];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int c = 0; c < NKB; ++c)
+        for (int c = 0; c < NBLK; ++c)
 #pragma unroll
             for (int v = 0; v < 16; ++v) e[rb][c][v] = 0.f;
 
-    // ---- prologue of the chunk pipeline
-    fetch_chunk();
-    stage_chunk(0);
-    if (nchunks > 1) fetch_chunk();
+    // LDS read offset of this lane inside a 32-key block: row l32, piece (2*ks + half) ^ swz
+    const int a_row_off = l32 * (D * 2);
+    const int a_hs = half ^ swz<D>(l32);
+
+    // ---- prologue: PF chunks in flight, query rows of layer 0
+    int n_issued = 0, n_done = 0;
+#pragma unroll
+    for (int i = 0; i < PF; ++i)
+        if (n_issued < nchunks) {
+            issue_chunk(i);
+            ++n_issued;
+        }
     load_q(0);
-    __syncthreads();
 
     const float cs = p.c;
-    int n = 0;
     float f_prev[RB], mrg_prev[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) f_prev[rb] = mrg_prev[rb] = 1.f;
 
+    int step = 0;   // layer steps done; its parity selects the ring half when NBUF == 2*NC
     for (int tile = 0; tile < ntiles; ++tile) {
         const int tile_key0 = key_begin + tile * C::KT;
         const bool ragged = tile_key0 + C::KT > key_end;
         const bool last_tile = tile == ntiles - 1;
-        for (int l = 0; l < L; ++l) {
+
+        // One layer step; par (the step's parity) is a constant in each inlined copy, so
+        // every ring slot named below is a fixed LDS object.
+        auto layer_step = [&](const int par, const int l) __attribute__((always_inline)) {
             float4 rec[RB];
             float mcur[RB], tz[RB], tn[RB], tc[RB];
 #pragma unroll
@@ -169,63 +215,88 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 mcur[rb] = rec[rb].x;
                 tz[rb] = tn[rb] = tc[rb] = 0.f;
             }
+            const int ring_half = (NBUF == NC) ? 0 : par * NC;
 #pragma unroll
-            for (int c = 0; c < NKB; ++c) {
-                const int buf = n & 1;
-                if (n + 1 < nchunks) stage_chunk(buf ^ 1);
-                if (n + 2 < nchunks) fetch_chunk();
+            for (int c = 0; c < NC; ++c) {
+                // Chunk (step, c) must have landed.  Loads return in order, so it is enough
+                // that no more loads are outstanding than the younger chunks account for.
+                const int younger = n_issued - 1 - n_done;
+                if (PF >= 3 && younger >= 2)
+                    __builtin_amdgcn_s_waitcnt(wait_vm(2 * NLD));
+                else if (PF >= 2 && younger == 1)
+                    __builtin_amdgcn_s_waitcnt(wait_vm(NLD));
+                else
+                    __builtin_amdgcn_s_waitcnt(wait_vm(0));
+                __builtin_amdgcn_s_barrier();
+                ++n_done;
+                const bool more = n_issued < nchunks;
+                if (c != NC - 1 && more) {
+                    issue_chunk((ring_half + c + PF) % NBUF);
+                    ++n_issued;
+                }
 
-                f32x16 acc[RB];
+                const unsigned char *slot = slot_ptr(ring_half + c);
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
-                const unsigned char *kb = &lds[buf][(wk * 32 + l32) * C::ROWB + half * 16];
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kb + ks * 32);
+                for (int kb = 0; kb < KBW; ++kb) {
+                    const int blk = c * KBW + kb;
+                    f32x16 acc[RB];
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
-                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][ks], acc[rb], 0, 0, 0);
-                }
-                if (c == NKB - 1) load_q(l + 1 == L ? 0 : l + 1);   // next step's query rows
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
+                    const unsigned char *kbp = slot + (wk * KBW + kb) * 32 * (D * 2) + a_row_off;
+                    bf16x8 a[KS];
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        a[ks] = *reinterpret_cast<const bf16x8 *>(kbp + (((2 * ks) ^ a_hs) << 4));
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb)
+                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qf[rb][ks], acc[rb], 0, 0, 0);
+                    if (c == NC - 1 && kb == KBW - 1) {
+                        load_q(l + 1 == L ? 0 : l + 1);   // next step's query rows
+                        if (more) {                        // ring loads stay the youngest loads
+                            issue_chunk((ring_half + c + PF) % NBUF);
+                            ++n_issued;
+                        }
+                    }
 
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb) {
-                    if (ragged) {
-                        const int kb0 = tile_key0 + c * C::CH + wk * 32 + half * 4;
+                    for (int rb = 0; rb < RB; ++rb) {
+                        if (ragged) {
+                            const int kb0 = tile_key0 + c * C::CH + (wk * KBW + kb) * 32 + half * 4;
 #pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            if (kb0 + 8 * (v >> 2) + (v & 3) >= key_end) acc[rb][v] = -INFINITY;
-                    }
-                    float tmax = acc[rb][0];
+                            for (int v = 0; v < 16; ++v)
+                                if (kb0 + 8 * (v >> 2) + (v & 3) >= key_end) acc[rb][v] = -INFINITY;
+                        }
+                        float tmax = acc[rb][0];
 #pragma unroll
-                    for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[rb][v]);
-                    const float xm = tmax * cs;
-                    if (__any(xm > mcur[rb] + kLazy)) {
-                        const float mnew = fmaxf(mcur[rb], xm);
-                        const float f = __builtin_amdgcn_exp2f(mcur[rb] - mnew);
-                        tz[rb] *= f;
-                        tn[rb] *= f * f;
-                        tc[rb] *= f;
+                        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[rb][v]);
+                        const float xm = tmax * cs;
+                        if (__any(xm > mcur[rb] + kLazy)) {
+                            const float mnew = fmaxf(mcur[rb], xm);
+                            const float f = __builtin_amdgcn_exp2f(mcur[rb] - mnew);
+                            tz[rb] *= f;
+                            tn[rb] *= f * f;
+                            tc[rb] *= f;
 #pragma unroll
-                        for (int cc = 0; cc < c; ++cc)
+                            for (int cc = 0; cc < blk; ++cc)
 #pragma unroll
-                            for (int v = 0; v < 16; ++v) e[rb][cc][v] *= f;
-                        mcur[rb] = mnew;
-                    }
-                    const float negm = -mcur[rb];
+                                for (int v = 0; v < 16; ++v) e[rb][cc][v] *= f;
+                            mcur[rb] = mnew;
+                        }
+                        const float negm = -mcur[rb];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float ev = __builtin_amdgcn_exp2f(fmaf(acc[rb][v], cs, negm));
-                        tz[rb] += ev;
-                        tn[rb] = fmaf(ev, ev, tn[rb]);
-                        tc[rb] = fmaf(ev, e[rb][c][v], tc[rb]);
-                        e[rb][c][v] = ev;
+                        for (int v = 0; v < 16; ++v) {
+                            const float ev = __builtin_amdgcn_exp2f(fmaf(acc[rb][v], cs, negm));
+                            tz[rb] += ev;
+                            tn[rb] = fmaf(ev, ev, tn[rb]);
+                            tc[rb] = fmaf(ev, e[rb][blk][v], tc[rb]);
+                            e[rb][blk][v] = ev;
+                        }
                     }
                 }
-                __syncthreads();
-                ++n;
             }
 
             // ---- fold this tile's sums into the running record of layer l
@@ -244,54 +315,69 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 for (int rb = 0; rb < RB; ++rb) spill[spill_index(l, rb)] = out[rb];
             } else {
                 // ---- merge the 2*WK partials of each row: common exponent, then sums
-                float mh[RB];
+                float M[RB];
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb) {
-                    mh[rb] = fmaxf(out[rb].x, __shfl_xor(out[rb].x, 32, 64));
-                    if (half == 0) red[wave][rb][0][l32] = mh[rb];
+                for (int rb = 0; rb < RB; ++rb) M[rb] = fmaxf(out[rb].x, __shfl_xor(out[rb].x, 32, 64));
+                if (WK > 1) {
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        if (half == 0) red[wave][rb][0][l32] = M[rb];
+                    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+                    __builtin_amdgcn_s_barrier();
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) {
+                        M[rb] = red[wr * WK][rb][0][l32];
+#pragma unroll
+                        for (int w2 = 1; w2 < WK; ++w2) M[rb] = fmaxf(M[rb], red[wr * WK + w2][rb][0][l32]);
+                    }
                 }
-                __syncthreads();
-                float zs[RB], ns[RB], cc2[RB], M[RB];
+                float zs[RB], ns[RB], cc2[RB];
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) {
-                    M[rb] = red[wr * WK][rb][0][l32];
-#pragma unroll
-                    for (int w2 = 1; w2 < WK; ++w2) M[rb] = fmaxf(M[rb], red[wr * WK + w2][rb][0][l32]);
                     const float f = __builtin_amdgcn_exp2f(out[rb].x - M[rb]);
                     float z = out[rb].y * f, nn = out[rb].z * f * f, cc = out[rb].w * f * mrg_prev[rb];
                     mrg_prev[rb] = f;
-                    z += __shfl_xor(z, 32, 64);
-                    nn += __shfl_xor(nn, 32, 64);
-                    cc += __shfl_xor(cc, 32, 64);
-                    zs[rb] = z;
-                    ns[rb] = nn;
-                    cc2[rb] = cc;
+                    zs[rb] = z + __shfl_xor(z, 32, 64);
+                    ns[rb] = nn + __shfl_xor(nn, 32, 64);
+                    cc2[rb] = cc + __shfl_xor(cc, 32, 64);
                 }
-                __syncthreads();
+                if (WK > 1) {
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-                    if (half == 0) {
-                        red[wave][rb][1][l32] = zs[rb];
-                        red[wave][rb][2][l32] = ns[rb];
-                        red[wave][rb][3][l32] = cc2[rb];
+                    for (int rb = 0; rb < RB; ++rb)
+                        if (half == 0) {
+                            red[wave][rb][1][l32] = zs[rb];
+                            red[wave][rb][2][l32] = ns[rb];
+                            red[wave][rb][3][l32] = cc2[rb];
+                        }
+                    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+                    __builtin_amdgcn_s_barrier();
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) {
+                        zs[rb] = ns[rb] = cc2[rb] = 0.f;
+#pragma unroll
+                        for (int w2 = 0; w2 < WK; ++w2) {
+                            zs[rb] += red[wr * WK + w2][rb][1][l32];
+                            ns[rb] += red[wr * WK + w2][rb][2][l32];
+                            cc2[rb] += red[wr * WK + w2][rb][3][l32];
+                        }
                     }
-                __syncthreads();
+                    // red is next written after the following layer step's chunk barriers
+                }
                 if (wk == 0 && half == 0) {
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) {
-                        float z = 0.f, nn = 0.f, cc = 0.f;
-#pragma unroll
-                        for (int w2 = 0; w2 < WK; ++w2) {
-                            z += red[wr * WK + w2][rb][1][l32];
-                            nn += red[wr * WK + w2][rb][2][l32];
-                            cc += red[wr * WK + w2][rb][3][l32];
-                        }
                         const size_t idx = ((size_t)wg * L + l) * C::R_WG + (wr * RB + rb) * 32 + l32;
-                        p.state[idx] = make_float4(M[rb], z, nn, cc);
+                        p.state[idx] = make_float4(M[rb], zs[rb], ns[rb], cc2[rb]);
                     }
                 }
-                __syncthreads();
             }
+        };
+
+        for (int l = 0; l < L; ++l, ++step) {
+            if (NBUF == NC || !(step & 1))
+                layer_step(0, l);
+            else
+                layer_step(1, l);
         }
     }
 }
@@ -305,19 +391,25 @@ hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
 
 }  // namespace
 
+// Tile shapes (rows x keys per workgroup tile) must match make_plan().
+//           D  WR WK RB KBW NC NBUF
+typedef Cfg<128, 4, 1, 1, 2, 2, 4> Wide128;   // 128 x 128, ring 4 x 64 keys (64 KB)
+typedef Cfg<64, 4, 1, 1, 2, 2, 4> Wide64;
+typedef Cfg<128, 1, 4, 2, 1, 2, 2> Mid128;    //  64 x 256, ring 2 x 128 keys (64 KB)
+typedef Cfg<64, 1, 4, 2, 1, 2, 4> Mid64;
+typedef Cfg<128, 1, 4, 1, 1, 4, 4> Slim128;   //  32 x 512, ring 4 x 128 keys (128 KB)
+typedef Cfg<64, 1, 4, 1, 1, 4, 4> Slim64;
+
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
 {
     const bool d128 = p.d == 128;
     switch (p.lay.variant) {
     case kMfmaWide:
-        return d128 ? launch_cfg<Cfg<128, 2, 2, 2, 2>>(p, n_workgroups, st)
-                    : launch_cfg<Cfg<64, 2, 2, 2, 2>>(p, n_workgroups, st);
+        return d128 ? launch_cfg<Wide128>(p, n_workgroups, st) : launch_cfg<Wide64>(p, n_workgroups, st);
     case kMfmaMid:
-        return d128 ? launch_cfg<Cfg<128, 1, 4, 2, 2>>(p, n_workgroups, st)
-                    : launch_cfg<Cfg<64, 1, 4, 2, 2>>(p, n_workgroups, st);
+        return d128 ? launch_cfg<Mid128>(p, n_workgroups, st) : launch_cfg<Mid64>(p, n_workgroups, st);
     case kMfmaSlim:
-        return d128 ? launch_cfg<Cfg<128, 1, 4, 1, 4>>(p, n_workgroups, st)
-                    : launch_cfg<Cfg<64, 1, 4, 1, 4>>(p, n_workgroups, st);
+        return d128 ? launch_cfg<Slim128>(p, n_workgroups, st) : launch_cfg<Slim64>(p, n_workgroups, st);
     default:
         return hipErrorInvalidValue;
     }
