@@ -7,7 +7,7 @@
 namespace krul {
 namespace {
 
-constexpr int kTargetWorkgroups = 512;   // two resident workgroups on each of 256 CUs
+constexpr int kTargetWorkgroups = 512;   // eight waves' worth of workgroups on each of 256 CUs, twice
 constexpr size_t kAlign = 256;
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -48,8 +48,8 @@ int make_plan(const krul_shape_t *s, Plan *pl)
     long long n_wg, records, spill_records = 0;
     if (mfma) {
         int kt;
-        if (Rk <= 32) { y.variant = kMfmaSlim; y.wr = 1; y.wk = 4; y.rb = 1; kt = 512; }
-        else if (Rk <= 64) { y.variant = kMfmaMid; y.wr = 1; y.wk = 4; y.rb = 2; kt = 256; }
+        if (Rk <= 32) { y.variant = kMfmaSlim; y.wr = 1; y.wk = 8; y.rb = 1; kt = 512; }
+        else if (Rk <= 64) { y.variant = kMfmaMid; y.wr = 2; y.wk = 4; y.rb = 1; kt = 512; }
         else { y.variant = kMfmaWide; y.wr = 4; y.wk = 1; y.rb = 1; kt = 128; }
         const long long r_wg = y.wr * y.rb * 32;
         const long long nrt = (Rk + r_wg - 1) / r_wg;
@@ -66,7 +66,7 @@ int make_plan(const krul_shape_t *s, Plan *pl)
         pl->keys_per_split = (int)(tps * kt);
         n_wg = units * nsplit;
         records = n_wg * L * r_wg;
-        if (tps > 1) spill_records = n_wg * L * 4 * y.rb * 64;
+        if (tps > 1) spill_records = n_wg * L * (y.wr * y.wk) * y.rb * 64;
     } else {
         y.variant = kGeneric;
         y.wr = y.wk = y.rb = 1;

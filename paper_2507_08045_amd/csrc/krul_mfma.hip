@@ -1,7 +1,7 @@
 // bf16 MFMA similarity kernel for gfx950 (CDNA4).
 //
 // Work decomposition.  A "unit" is one (conversation, kv head): its (Hq/Hkv)*Tq
-// query rows all read the same keys.  A workgroup (4 wavefronts) owns R_WG rows of a
+// query rows all read the same keys.  A workgroup (4 or 8 wavefronts) owns R_WG rows of a
 // unit and one contiguous key split; it walks the split in key tiles of KT keys and,
 // inside a tile, the layers 0..L-1 in order, so that every layer's logits are formed
 // exactly once and the previous layer's exponentials of the same keys are still in
@@ -26,10 +26,13 @@
 // are independent partials of a row, merged once after the last tile.
 //
 // Online softmax uses a lazily updated reference exponent m per (lane, layer): it is
-// raised only when a logit exceeds it by more than kLazy (in log2 units); then the
-// running sums, and the exponentials of the current layer already produced in this
-// tile, are rescaled.  Cosine and distance are invariant to the choice of m, and
-// e = 2^(x-m) <= 2^kLazy keeps every sum far inside fp32 range.
+// raised only when a logit exceeds it by more than kLazy (in log2 units); the running
+// sums Z and N2 are then rescaled.  The exponentials kept for the next layer's cross
+// term are NOT rescaled: each 32-key block remembers the exponent it was formed under,
+// the block's dot product with the next layer is kept apart, and the per-block factors
+// of both layers are applied when the layer step ends.  Cosine and distance are
+// invariant to the choice of m, and e = 2^(x-m) <= 2^kLazy keeps every sum far inside
+// fp32 range.
 #include "krul_common.h"
 
 namespace krul {
@@ -54,7 +57,7 @@ struct Cfg {
     static constexpr int SLOT_BYTES = CH * D * 2;
     static constexpr int NLD = CH * PPR / THREADS; // direct-to-LDS loads per thread per chunk
     static constexpr int PF = NBUF - 1;            // chunks in flight ahead of the compute
-    static_assert(NW == 4, "four waves per workgroup");
+    static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
     static_assert(CH * PPR % THREADS == 0, "chunk must split evenly over threads");
     static_assert(NBUF == NC || NBUF == 2 * NC, "ring must be one or two tiles deep");
     static_assert(NBUF >= 2 && NBUF <= 4, "two to four ring slots");
@@ -99,7 +102,8 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         }
     };
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
     const int wr = wave / WK, wk = wave % WK, half = lane >> 5, l32 = lane & 31;
 
     const int wg = xcd_remap(blockIdx.x, gridDim.x);
@@ -119,38 +123,47 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     const size_t q_layer_stride = (size_t)p.Hq * p.Tq * D;
     const size_t k_layer_stride = (size_t)p.Hkv * S * D;
     const uint16_t *qbase = Qg + ((size_t)b * L * p.Hq * p.Tq + (size_t)kvh * Rk) * D;
-    int qoff[RB];   // element offset of this lane's query row inside a layer
+    unsigned qoff[RB];   // element offset of this lane's query row inside a layer
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
-        qoff[rb] = min(rt * C::R_WG + (wr * RB + rb) * 32 + l32, Rk - 1) * D + half * 8;
+        qoff[rb] = (unsigned)(min(rt * C::R_WG + (wr * RB + rb) * 32 + l32, Rk - 1) * D + half * 8);
     const uint16_t *kbase = Kg + ((size_t)b * L * p.Hkv + kvh) * (size_t)S * D;
 
     // ---- K ring: wave-instruction j of this wave fills granules [(wave*NLD+j)*64, +64)
     // of a slot; the lane at granule g = row*PPR + pc fetches piece pc ^ swz(row) of row.
-    int ld_row[NLD], ld_col[NLD];
-#pragma unroll
-    for (int j = 0; j < NLD; ++j) {
-        const int g = (wave * NLD + j) * 64 + lane;
-        ld_row[j] = g / PPR;
-        ld_col[j] = ((g % PPR) ^ swz<D>(g / PPR)) * 8;
-    }
+    // One wave-instruction covers 64/PPR whole rows (1 KB).  For instruction j the row is
+    // ld_row0 + j*(64/PPR) (the j*1 KB step goes into the scalar offset of the load);
+    // j*(64/PPR) occupies bits of the row number that are zero in
+    // ld_row0 (all extents are powers of two), so the swizzle of row j is that of row 0
+    // with xj(j) xor-ed in: one register (ld_off0) describes all of a lane's copies.
+    constexpr int RPI = 64 / PPR;   // rows per wave-instruction
+    const int ld_row0 = wave * NLD * RPI + lane / PPR;
+    const int ld_colb0 = ((lane % PPR) ^ swz<D>(ld_row0)) * 16;
+    const unsigned ld_off0 = (unsigned)(ld_row0 * (D * 2) + ld_colb0);   // unsigned: base + 32-bit offset addressing
+    auto xj = [](int j) -> unsigned { return (unsigned)((D == 128 ? ((j * RPI) & 15) : (((j * RPI) >> 1) & 7)) * 16); };
     int pf_tile = 0, pf_l = 0, pf_c = 0;   // next chunk to fetch
     auto issue_chunk = [&](int slot) __attribute__((always_inline)) {
         unsigned char *dst = slot_ptr(slot);
         const int key0 = key_begin + pf_tile * C::KT + pf_c * C::CH;
-        const uint16_t *src = kbase + (size_t)pf_l * k_layer_stride;
+        // Buffer addressing: a scalar descriptor for the rest of this layer's keys (rows past
+        // the last key are out of range and are not fetched), one 32-bit offset per lane.
+        const uint16_t *src = kbase + (size_t)pf_l * k_layer_stride + (size_t)key0 * D;
+        const unsigned bytes = (unsigned)max(S - key0, 0) * (unsigned)(D * 2);
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(src), 0, (int)bytes, 0x00020000);
 #pragma unroll
-        for (int j = 0; j < NLD; ++j) {
-            const int key = min(key0 + ld_row[j], S - 1);
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(src + (size_t)key * D + ld_col[j]),
-                (__attribute__((address_space(3))) void *)(dst + (wave * NLD + j) * 1024), 16, 0, 0);
-        }
-        if (++pf_c == NC) {
+        for (int j = 0; j < NLD; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rsrc, (__attribute__((address_space(3))) void *)(dst + (wave * NLD + j) * 1024), 16,
+                (int)(ld_off0 ^ xj(j)), j * 1024, 0, 0);
+        // (the counters are wave-uniform; say so, to keep them in scalar registers)
+        pf_c = pf_c + 1;
+        if (pf_c == NC) {
             pf_c = 0;
-            if (++pf_l == L) {
+            pf_l = pf_l + 1;
+            if (pf_l == L) {
                 pf_l = 0;
-                ++pf_tile;
+                pf_tile = pf_tile + 1;
             }
         }
     };
@@ -180,8 +193,8 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
             for (int v = 0; v < 16; ++v) e[rb][c][v] = 0.f;
 
     // LDS read offset of this lane inside a 32-key block: row l32, piece (2*ks + half) ^ swz
-    const int a_row_off = l32 * (D * 2);
-    const int a_hs = half ^ swz<D>(l32);
+    // = l32*(D*2) + (((2*ks) ^ a_hs) << 4) = a_base ^ (ks << 5), a_hs = half ^ swz(l32)
+    const int a_base = l32 * (D * 2) + ((half ^ swz<D>(l32)) << 4);
 
     // ---- prologue: PF chunks in flight, query rows of layer 0
     int n_issued = 0, n_done = 0;
@@ -195,8 +208,14 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
     const float cs = p.c;
     float f_prev[RB], mrg_prev[RB];
+    float sprev[RB][NBLK];    // previous layer step: 2^(block exponent - final exponent)
+    bool raised_prev = false;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) f_prev[rb] = mrg_prev[rb] = 1.f;
+    for (int rb = 0; rb < RB; ++rb) {
+        f_prev[rb] = mrg_prev[rb] = 1.f;
+#pragma unroll
+        for (int k2 = 0; k2 < NBLK; ++k2) sprev[rb][k2] = 1.f;
+    }
 
     int step = 0;   // layer steps done; its parity selects the ring half when NBUF == 2*NC
     for (int tile = 0; tile < ntiles; ++tile) {
@@ -208,12 +227,14 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         // every ring slot named below is a fixed LDS object.
         auto layer_step = [&](const int par, const int l) __attribute__((always_inline)) {
             float4 rec[RB];
-            float mcur[RB], tz[RB], tn[RB], tc[RB];
+            float mcur[RB], tz[RB], tn[RB];
+            float mb[RB][NBLK], dot[RB][NBLK];   // per block: exponent used, dot with previous layer
+            bool raised = false;                 // some lane raised m during this step (wave-uniform)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 rec[rb] = tile > 0 ? spill[spill_index(l, rb)] : make_float4(kMInit, 0.f, 0.f, 0.f);
                 mcur[rb] = rec[rb].x;
-                tz[rb] = tn[rb] = tc[rb] = 0.f;
+                tz[rb] = tn[rb] = 0.f;
             }
             const int ring_half = (NBUF == NC) ? 0 : par * NC;
 #pragma unroll
@@ -228,11 +249,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 else
                     __builtin_amdgcn_s_waitcnt(wait_vm(0));
                 __builtin_amdgcn_s_barrier();
-                ++n_done;
+                n_done = n_done + 1;
                 const bool more = n_issued < nchunks;
                 if (c != NC - 1 && more) {
                     issue_chunk((ring_half + c + PF) % NBUF);
-                    ++n_issued;
+                    n_issued = n_issued + 1;
                 }
 
                 const unsigned char *slot = slot_ptr(ring_half + c);
@@ -244,31 +265,36 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                         for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
-                    const unsigned char *kbp = slot + (wk * KBW + kb) * 32 * (D * 2) + a_row_off;
+                    const unsigned char *kbp = slot + (wk * KBW + kb) * 32 * (D * 2);
                     bf16x8 a[KS];
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks)
-                        a[ks] = *reinterpret_cast<const bf16x8 *>(kbp + (((2 * ks) ^ a_hs) << 4));
+                        a[ks] = *reinterpret_cast<const bf16x8 *>(kbp + (a_base ^ (ks << 5)));
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                         for (int rb = 0; rb < RB; ++rb)
                             acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qf[rb][ks], acc[rb], 0, 0, 0);
                     if (c == NC - 1 && kb == KBW - 1) {
+                        // the old query rows are dead once the MFMAs above have issued; do not
+                        // let the loads below be scheduled ahead of them (they would need a
+                        // second set of registers)
                         load_q(l + 1 == L ? 0 : l + 1);   // next step's query rows
                         if (more) {                        // ring loads stay the youngest loads
                             issue_chunk((ring_half + c + PF) % NBUF);
-                            ++n_issued;
+                            n_issued = n_issued + 1;
                         }
                     }
 
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) {
                         if (ragged) {
-                            const int kb0 = tile_key0 + c * C::CH + (wk * KBW + kb) * 32 + half * 4;
+                            // keys at or past key_end: element v of this lane is key kb0 + 8*(v/4) + v%4
+                            int lim = key_end - (tile_key0 + c * C::CH + (wk * KBW + kb) * 32 + half * 4);
+                            asm volatile("" : "+v"(lim));   // keep the 16 compares here, not hoisted
 #pragma unroll
                             for (int v = 0; v < 16; ++v)
-                                if (kb0 + 8 * (v >> 2) + (v & 3) >= key_end) acc[rb][v] = -INFINITY;
+                                if (8 * (v >> 2) + (v & 3) >= lim) acc[rb][v] = -INFINITY;
                         }
                         float tmax = acc[rb][0];
 #pragma unroll
@@ -279,25 +305,50 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                             const float f = __builtin_amdgcn_exp2f(mcur[rb] - mnew);
                             tz[rb] *= f;
                             tn[rb] *= f * f;
-                            tc[rb] *= f;
-#pragma unroll
-                            for (int cc = 0; cc < blk; ++cc)
-#pragma unroll
-                                for (int v = 0; v < 16; ++v) e[rb][cc][v] *= f;
                             mcur[rb] = mnew;
+                            raised = true;
                         }
+                        mb[rb][blk] = mcur[rb];
                         const float negm = -mcur[rb];
+                        float bz = 0.f, bn = 0.f, bd = 0.f;
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             const float ev = __builtin_amdgcn_exp2f(fmaf(acc[rb][v], cs, negm));
-                            tz[rb] += ev;
-                            tn[rb] = fmaf(ev, ev, tn[rb]);
-                            tc[rb] = fmaf(ev, e[rb][blk][v], tc[rb]);
+                            bz += ev;
+                            bn = fmaf(ev, ev, bn);
+                            bd = fmaf(ev, e[rb][blk][v], bd);
                             e[rb][blk][v] = ev;
                         }
+                        tz[rb] += bz;
+                        tn[rb] += bn;
+                        dot[rb][blk] = bd;
                     }
                 }
             }
+
+            // ---- cross term of this tile: block dots, each brought to the final exponents of
+            // both layers (the factors are 1 unless some m was raised in this or the last step)
+            float tc[RB];
+            if (raised || raised_prev) {
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    tc[rb] = 0.f;
+#pragma unroll
+                    for (int k2 = 0; k2 < NBLK; ++k2) {
+                        const float sc = __builtin_amdgcn_exp2f(mb[rb][k2] - mcur[rb]);
+                        tc[rb] = fmaf(dot[rb][k2], sc * sprev[rb][k2], tc[rb]);
+                        sprev[rb][k2] = sc;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    tc[rb] = 0.f;
+#pragma unroll
+                    for (int k2 = 0; k2 < NBLK; ++k2) tc[rb] += dot[rb][k2];
+                }
+            }
+            raised_prev = raised;
 
             // ---- fold this tile's sums into the running record of layer l
             float4 out[RB];
@@ -321,7 +372,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 if (WK > 1) {
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
-                        if (half == 0) red[wave][rb][0][l32] = M[rb];
+                        red[wave][rb][0][l32] = M[rb];   // both half-waves hold the same value
                     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
                     __builtin_amdgcn_s_barrier();
 #pragma unroll
@@ -343,12 +394,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 }
                 if (WK > 1) {
 #pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-                        if (half == 0) {
-                            red[wave][rb][1][l32] = zs[rb];
-                            red[wave][rb][2][l32] = ns[rb];
-                            red[wave][rb][3][l32] = cc2[rb];
-                        }
+                    for (int rb = 0; rb < RB; ++rb) {   // both half-waves hold the same sums
+                        red[wave][rb][1][l32] = zs[rb];
+                        red[wave][rb][2][l32] = ns[rb];
+                        red[wave][rb][3][l32] = cc2[rb];
+                    }
                     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
                     __builtin_amdgcn_s_barrier();
 #pragma unroll
@@ -363,7 +413,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                     }
                     // red is next written after the following layer step's chunk barriers
                 }
-                if (wk == 0 && half == 0) {
+                if (wk == 0) {   // wave-uniform; lanes l and l+32 store the same record
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) {
                         const size_t idx = ((size_t)wg * L + l) * C::R_WG + (wr * RB + rb) * 32 + l32;
@@ -393,12 +443,12 @@ hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
 
 // Tile shapes (rows x keys per workgroup tile) must match make_plan().
 //           D  WR WK RB KBW NC NBUF
-typedef Cfg<128, 4, 1, 1, 2, 2, 4> Wide128;   // 128 x 128, ring 4 x 64 keys (64 KB)
+typedef Cfg<128, 4, 1, 1, 2, 2, 4> Wide128;   // 128 x 128, 4 waves, ring 4 x  64 keys ( 64 KB)
 typedef Cfg<64, 4, 1, 1, 2, 2, 4> Wide64;
-typedef Cfg<128, 1, 4, 2, 1, 2, 2> Mid128;    //  64 x 256, ring 2 x 128 keys (64 KB)
-typedef Cfg<64, 1, 4, 2, 1, 2, 4> Mid64;
-typedef Cfg<128, 1, 4, 1, 1, 4, 4> Slim128;   //  32 x 512, ring 4 x 128 keys (128 KB)
-typedef Cfg<64, 1, 4, 1, 1, 4, 4> Slim64;
+typedef Cfg<128, 2, 4, 1, 2, 2, 2> Mid128;    //  64 x 512, 8 waves, ring 2 x 256 keys (128 KB)
+typedef Cfg<64, 2, 4, 1, 2, 2, 4> Mid64;      //  64 x 512, 8 waves, ring 4 x 256 keys (128 KB)
+typedef Cfg<128, 1, 8, 1, 1, 2, 2> Slim128;   //  32 x 512, 8 waves, ring 2 x 256 keys (128 KB)
+typedef Cfg<64, 1, 8, 1, 1, 2, 4> Slim64;     //  32 x 512, 8 waves, ring 4 x 256 keys (128 KB)
 
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
 {
