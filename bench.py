@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run the library's plain copy kernel on MIB MiB a few times (a known-size "
+                         "reference for rocprofv3 traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only; --gpus above 1 is not supported "
@@ -115,6 +118,13 @@ def main():
         step(evs[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+
+    if args.copy_calibration > 0:
+        a = torch.empty(args.copy_calibration << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        b = torch.empty_like(a)
+        for _ in range(5):
+            kr.calibration_copy(a, b)
+        torch.cuda.synchronize()
 
     kern_ms = [hipevents.elapsed_ms(a, b) for a, b in evs]
     for a, b in evs:

@@ -135,6 +135,14 @@ int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
  */
 int32_t krul_n_select_from_ratio(int32_t n_layers, float r_l);
 
+/*
+ * Measurement aid: a plain device-to-device copy kernel (src -> dst, both device, 16-byte
+ * aligned, bytes a multiple of 16) on the caller's stream.  It reads `bytes` and writes
+ * `bytes` of HBM and nothing else, which gives hardware traffic counters a known reference
+ * to be scaled by when the similarity kernel's HBM traffic is measured.
+ */
+int krul_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 /* Static description of a status code.  Host-only. */
 const char *krul_strerror(int status);
 

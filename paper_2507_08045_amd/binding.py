@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_timed.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
         L.krul_select_pairs.restype = ctypes.c_int
         L.krul_select_pairs.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+        L.krul_calibration_copy.restype = ctypes.c_int
+        L.krul_calibration_copy.argtypes = [vp, vp, sz, vp]
         L.krul_n_select_from_ratio.restype = i32
         L.krul_n_select_from_ratio.argtypes = [i32, ctypes.c_float]
         L.krul_strerror.restype = ctypes.c_char_p
@@ -166,3 +168,15 @@ def select_pairs(pair_score: torch.Tensor, n_select: int, eligible: torch.Tensor
     if rc != KRUL_OK:
         raise KrulError(rc)
     return out_pairs, out_count
+
+
+def calibration_copy(src: torch.Tensor, dst: torch.Tensor):
+    """krul_calibration_copy: plain copy kernel of known size (reference for traffic counters)."""
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("src and dst must be contiguous GPU tensors")
+    n = src.numel() * src.element_size()
+    if n != dst.numel() * dst.element_size():
+        raise ValueError("src and dst must have the same size in bytes")
+    rc = lib().krul_calibration_copy(_dev_ptr(src), _dev_ptr(dst), n, ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)

@@ -100,7 +100,25 @@ int make_plan(const krul_shape_t *s, Plan *pl)
 
 using namespace krul;
 
+namespace {
+__global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__restrict__ src,
+                                                               uint4 *__restrict__ dst, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+}  // namespace
+
 extern "C" {
+
+int krul_calibration_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst || bytes == 0 || (bytes & 15) || (((uintptr_t)src | (uintptr_t)dst) & 15))
+        return KRUL_EINVAL;
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(256 * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), bytes / 16);
+    return hipGetLastError() == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
+}
 
 size_t krul_pair_similarity_workspace(const krul_shape_t *shape)
 {

@@ -1,11 +1,11 @@
 // Row similarity and token-wise aggregation (Sec. 5 / Sec. 7: per-token similarities
 // are added up; Sec. 4.2: the average over heads).
 //
-// finalize_heads: one workgroup per (conversation, pair, query head).  Each thread
-// takes query rows t, t+256, ...: it merges the row's partial records of the two
-// layers onto a common reference exponent, forms the cosine and (from the
-// a^2 + b^2 - 2ab expansion of Sec. 7) the Euclidean distance of the two attention
-// rows, and the workgroup sums over rows in a fixed tree order.
+// finalize_heads: one workgroup per (conversation, pair, query head).  A few lanes
+// share each query row: they merge the row's partial records of the two layers
+// onto a common reference exponent (fixed butterfly order), form the cosine and
+// (from the a^2 + b^2 - 2ab expansion of Sec. 7) the Euclidean distance of the two
+// attention rows, and the workgroup sums over rows in a fixed tree order.
 // finalize_pairs: one thread per (conversation, pair) averages the heads in order.
 #include "krul_common.h"
 
@@ -27,8 +27,31 @@ __device__ inline float block_sum(float v, float *red)
     return s;
 }
 
+// Running merge of partial records of one row for a layer pair (a = layer l, b = l+1):
+// exponents Ma, Mb; Z and N2 of both layers and the cross term C, all relative to them.
+struct RowAcc {
+    float Ma, Za, Na, Mb, Zb, Nb, C;
+};
+
+__device__ inline void merge_into(RowAcc &r, float ma, float za, float na, float mb, float zb, float nb, float c)
+{
+    const float Ma = fmaxf(r.Ma, ma), Mb = fmaxf(r.Mb, mb);
+    const float fa0 = exp2f(r.Ma - Ma), fa1 = exp2f(ma - Ma);
+    const float fb0 = exp2f(r.Mb - Mb), fb1 = exp2f(mb - Mb);
+    r.Za = r.Za * fa0 + za * fa1;
+    r.Na = r.Na * (fa0 * fa0) + na * (fa1 * fa1);
+    r.Zb = r.Zb * fb0 + zb * fb1;
+    r.Nb = r.Nb * (fb0 * fb0) + nb * (fb1 * fb1);
+    r.C = r.C * (fa0 * fb0) + c * (fa1 * fb1);
+    r.Ma = Ma;
+    r.Mb = Mb;
+}
+
+// G lanes of a wave (G a power of two, lanes g*(64/G) + r for g < G) share one query row:
+// each merges the partials p = g, g+G, ... and a butterfly over g joins them.  Lanes with
+// the same g read consecutive rows, i.e. consecutive records.
 __global__ __launch_bounds__(kThreads) void finalize_heads_kernel(
-    StateLayout lay, const float4 *__restrict__ state, int L, int Hq, int Hkv, int Tq,
+    StateLayout lay, const float4 *__restrict__ state, int L, int Hq, int Hkv, int Tq, int G,
     float *__restrict__ head_cos, float *__restrict__ head_dist)
 {
     __shared__ float red[kThreads / 64];
@@ -36,35 +59,38 @@ __global__ __launch_bounds__(kThreads) void finalize_heads_kernel(
     const int h = blockIdx.x % Hq;
     const int l = (blockIdx.x / Hq) % NP;
     const int b = blockIdx.x / (Hq * NP);
-    const int g = Hq / Hkv;
-    const int u = b * Hkv + h / g;
+    const int g_heads = Hq / Hkv;
+    const int u = b * Hkv + h / g_heads;
     const int P = lay.partials;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int RW = 64 / G;                       // rows per wave
+    const int rr = lane % RW, g = lane / RW;
 
     float cos_acc = 0.f, dist_acc = 0.f;
-    for (int t = threadIdx.x; t < Tq; t += kThreads) {
-        const int r = (h % g) * Tq + t;
-        // pass 1: common reference exponents of the two layers
-        float Ma = kMInit, Mb = kMInit;
-        for (int p = 0; p < P; ++p) {
-            Ma = fmaxf(Ma, state[state_index(lay, u, r, p, l)].x);
-            Mb = fmaxf(Mb, state[state_index(lay, u, r, p, l + 1)].x);
+    for (int t0 = 0; t0 < Tq; t0 += (kThreads / 64) * RW) {
+        const int t = t0 + wave * RW + rr;
+        RowAcc acc = {kMInit, 0.f, 0.f, kMInit, 0.f, 0.f, 0.f};
+        if (t < Tq) {
+            const int r = (h % g_heads) * Tq + t;
+            for (int p = g; p < P; p += G) {
+                const float4 a = state[state_index(lay, u, r, p, l)];
+                const float4 c = state[state_index(lay, u, r, p, l + 1)];
+                merge_into(acc, a.x, a.y, a.z, c.x, c.y, c.z, c.w);
+            }
         }
-        // pass 2: rescale and add, partials in index order
-        float Za = 0.f, Na = 0.f, Zb = 0.f, Nb = 0.f, C = 0.f;
-        for (int p = 0; p < P; ++p) {
-            const float4 a = state[state_index(lay, u, r, p, l)];
-            const float4 c = state[state_index(lay, u, r, p, l + 1)];
-            const float fa = exp2f(a.x - Ma), fb = exp2f(c.x - Mb);
-            Za = fmaf(a.y, fa, Za);
-            Na = fmaf(a.z, fa * fa, Na);
-            Zb = fmaf(c.y, fb, Zb);
-            Nb = fmaf(c.z, fb * fb, Nb);
-            C = fmaf(c.w, fa * fb, C);
+        for (int off = 32; off >= RW; off >>= 1) {
+            const float ma = __shfl_xor(acc.Ma, off, 64), za = __shfl_xor(acc.Za, off, 64);
+            const float na = __shfl_xor(acc.Na, off, 64), mb = __shfl_xor(acc.Mb, off, 64);
+            const float zb = __shfl_xor(acc.Zb, off, 64), nb = __shfl_xor(acc.Nb, off, 64);
+            const float c = __shfl_xor(acc.C, off, 64);
+            merge_into(acc, ma, za, na, mb, zb, nb, c);
         }
-        cos_acc += C * rsqrtf(Na * Nb);
-        const float ia = 1.f / Za, ib = 1.f / Zb;
-        const float d2 = Na * ia * ia + Nb * ib * ib - 2.f * C * ia * ib;
-        dist_acc += sqrtf(fmaxf(d2, 0.f));
+        if (t < Tq && g == 0) {
+            cos_acc += acc.C * rsqrtf(acc.Na * acc.Nb);
+            const float ia = 1.f / acc.Za, ib = 1.f / acc.Zb;
+            const float d2 = acc.Na * ia * ia + acc.Nb * ib * ib - 2.f * acc.C * ia * ib;
+            dist_acc += sqrtf(fmaxf(d2, 0.f));
+        }
     }
     const float cs = block_sum(cos_acc, red);
     const float ds = block_sum(dist_acc, red);
@@ -96,8 +122,11 @@ hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, i
                            float *pair_dist, hipStream_t st)
 {
     const int n_pairs_total = B * (L - 1);
+    // lanes per row: enough to keep a workgroup's 256 threads busy, at most one per partial
+    int G = 1;
+    while (G < 64 && G * Tq < kThreads && G < lay.partials) G <<= 1;
     hipLaunchKernelGGL(finalize_heads_kernel, dim3(n_pairs_total * Hq), dim3(kThreads), 0, st, lay,
-                       state, L, Hq, Hkv, Tq, head_cos, head_dist);
+                       state, L, Hq, Hkv, Tq, G, head_cos, head_dist);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(finalize_pairs_kernel, dim3((n_pairs_total + 127) / 128), dim3(128), 0, st,

@@ -1,0 +1,128 @@
+"""Host-side checks of the C ABI that need no GPU: every function declared in
+include/krul.h is exported by libkrul.so, host-only helpers compute what the header
+says, and invalid arguments are rejected with the documented status before any GPU
+work is attempted."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def kr():
+    import paper_2507_08045_amd as kr_
+    if not os.path.exists(kr_.binding.LIB_PATH):
+        from paper_2507_08045_amd import build
+        build.build()
+    kr_.lib()
+    return kr_
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "krul.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(krul_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(kr):
+    names = declared_functions()
+    assert {"krul_pair_similarity", "krul_select_pairs", "krul_pair_similarity_workspace",
+            "krul_n_select_from_ratio", "krul_strerror", "krul_pair_similarity_timed"} <= set(names)
+    lib = kr.lib()
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in krul.h but not exported"
+
+
+def test_strerror_and_status_codes(kr):
+    assert kr.strerror(0) == "ok"
+    seen = {kr.strerror(c) for c in (0, -1, -2, -3, -4, -5)}
+    assert len(seen) == 6
+    assert kr.strerror(-99) == "unknown status"
+
+
+def test_n_select_from_ratio(kr):
+    # Alg. 1 stops when the shared set holds N*r_l layers, two per pair
+    assert kr.n_select_from_ratio(32, 0.5) == 8
+    assert kr.n_select_from_ratio(80, 0.5) == 20
+    assert kr.n_select_from_ratio(4, 0.5) == 1
+    assert kr.n_select_from_ratio(6, 1.0) == 3
+    assert kr.n_select_from_ratio(7, 1.0) == 3          # capped at N/2
+    assert kr.n_select_from_ratio(32, 0.0) == 0
+    assert kr.n_select_from_ratio(32, 0.3) == math.ceil(32 * 0.3 / 2)
+    assert kr.n_select_from_ratio(1, 0.5) == 0
+
+
+def shape(kr, B=1, L=4, Hq=4, Hkv=2, d=128, S=256, Tq=8, dtype=1, scale=0.0, flags=0):
+    return kr.KrulShape(B, L, Hq, Hkv, d, S, Tq, dtype, scale, flags)
+
+
+def test_workspace_query(kr):
+    for cfg in [dict(), dict(dtype=0, d=64), dict(S=100000, Tq=1), dict(L=80, Hq=64, Hkv=8, Tq=256, S=16384, B=8)]:
+        n = kr.workspace_bytes(shape(kr, **cfg))
+        assert n > 0 and n % 256 == 0
+    # the five benchmark configurations are all supported
+    import workloads
+    for name, (B, L, Hq, Hkv, d, S, Tq, dt, _) in workloads.CONFIGS.items():
+        assert kr.workspace_bytes(shape(kr, B, L, Hq, Hkv, d, S, Tq, 0 if dt == "f32" else 1)) > 0, name
+    bad = [dict(B=0), dict(L=1), dict(Hq=3, Hkv=2), dict(S=0), dict(Tq=0), dict(dtype=7), dict(d=100),
+           dict(d=512), dict(scale=-1.0), dict(scale=float("nan")), dict(flags=1), dict(L=5000)]
+    for cfg in bad:
+        assert kr.workspace_bytes(shape(kr, **cfg)) == 0, cfg
+
+
+def call_sim(kr, shp, q=0x1000, k=0x2000, ps=0x3000, hs=None, pd=None, ws=0x10000, ws_bytes=1 << 40):
+    vp = ctypes.c_void_p
+    return kr.lib().krul_pair_similarity(ctypes.byref(shp), vp(q), vp(k), vp(ps), vp(hs), vp(pd), vp(ws),
+                                         ctypes.c_size_t(ws_bytes), None)
+
+
+def test_pair_similarity_rejects_bad_arguments_before_any_gpu_work(kr):
+    ok = shape(kr)
+    need = kr.workspace_bytes(ok)
+    assert call_sim(kr, shape(kr, L=1)) == kr.KRUL_EINVAL
+    assert call_sim(kr, shape(kr, Hq=3)) == kr.KRUL_EINVAL
+    assert call_sim(kr, shape(kr, dtype=9)) == kr.KRUL_EDTYPE
+    assert call_sim(kr, shape(kr, d=100)) == kr.KRUL_EUNSUPPORTED
+    assert call_sim(kr, shape(kr, L=3000)) == kr.KRUL_EUNSUPPORTED
+    assert call_sim(kr, ok, q=None) == kr.KRUL_EINVAL
+    assert call_sim(kr, ok, k=None) == kr.KRUL_EINVAL
+    assert call_sim(kr, ok, ps=None) == kr.KRUL_EINVAL
+    assert call_sim(kr, ok, q=0x1008) == kr.KRUL_EINVAL            # 16-byte alignment
+    assert call_sim(kr, ok, ps=0x3002) == kr.KRUL_EINVAL           # float alignment
+    assert call_sim(kr, ok, ws=None) == kr.KRUL_EWORKSPACE
+    assert call_sim(kr, ok, ws=0x10010) == kr.KRUL_EWORKSPACE      # 256-byte alignment
+    assert call_sim(kr, ok, ws_bytes=need - 1) == kr.KRUL_EWORKSPACE
+    assert kr.lib().krul_pair_similarity(None, None, None, None, None, None, None, 0, None) == kr.KRUL_EINVAL
+
+
+def test_select_pairs_rejects_bad_arguments(kr):
+    vp = ctypes.c_void_p
+    f = kr.lib().krul_select_pairs
+    good = dict(ps=vp(0x1000), el=None, B=1, L=8, n=2, op=vp(0x2000), oc=vp(0x3000))
+
+    def call(**kw):
+        a = {**good, **kw}
+        return f(a["ps"], a["el"], a["B"], a["L"], a["n"], a["op"], a["oc"], None)
+    assert call(ps=None) == kr.KRUL_EINVAL
+    assert call(oc=None) == kr.KRUL_EINVAL
+    assert call(op=None) == kr.KRUL_EINVAL
+    assert call(B=0) == kr.KRUL_EINVAL
+    assert call(L=1) == kr.KRUL_EINVAL
+    assert call(n=-1) == kr.KRUL_EINVAL
+    assert call(n=5) == kr.KRUL_EINVAL              # more pairs than N/2
+    assert call(L=5000, n=1) == kr.KRUL_EUNSUPPORTED
+    assert call(ps=vp(0x1002)) == kr.KRUL_EINVAL
+
+
+def test_binding_refuses_cpu_tensors(kr):
+    import torch
+    q = torch.zeros((1, 2, 2, 2, 64), dtype=torch.bfloat16)
+    k = torch.zeros((1, 2, 2, 4, 64), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        kr.pair_similarity(q, k)
+    with pytest.raises(ValueError):
+        kr.select_pairs(torch.zeros((1, 3)), 1)
