@@ -241,10 +241,13 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
             for (int c = 0; c < NC; ++c) {
                 // Chunk (step, c) must have landed.  Loads return in order, so it is enough
                 // that no more loads are outstanding than the younger chunks account for.
+                // At the first chunk of a step the query rows loaded during the previous chunk
+                // (issued before that chunk's copy) must be complete too: allow one younger
+                // chunk only, which also tells the compiler's wait pass that they have landed.
                 const int younger = n_issued - 1 - n_done;
-                if (PF >= 3 && younger >= 2)
+                if (PF >= 3 && younger >= 2 && c != 0)
                     __builtin_amdgcn_s_waitcnt(wait_vm(2 * NLD));
-                else if (PF >= 2 && younger == 1)
+                else if (PF >= 2 && younger >= 1)
                     __builtin_amdgcn_s_waitcnt(wait_vm(NLD));
                 else
                     __builtin_amdgcn_s_waitcnt(wait_vm(0));
@@ -443,8 +446,8 @@ hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
 
 // Tile shapes (rows x keys per workgroup tile) must match make_plan().
 //           D  WR WK RB KBW NC NBUF
-typedef Cfg<128, 4, 1, 1, 2, 2, 4> Wide128;   // 128 x 128, 4 waves, ring 4 x  64 keys ( 64 KB)
-typedef Cfg<64, 4, 1, 1, 2, 2, 4> Wide64;
+typedef Cfg<128, 4, 1, 1, 2, 2, 2> Wide128;   // 128 x 128, 4 waves, ring 2 x  64 keys ( 32 KB)
+typedef Cfg<64, 4, 1, 1, 2, 2, 2> Wide64;
 typedef Cfg<128, 2, 4, 1, 2, 2, 2> Mid128;    //  64 x 512, 8 waves, ring 2 x 256 keys (128 KB)
 typedef Cfg<64, 2, 4, 1, 2, 2, 4> Mid64;      //  64 x 512, 8 waves, ring 4 x 256 keys (128 KB)
 typedef Cfg<128, 1, 8, 1, 1, 2, 2> Slim128;   //  32 x 512, 8 waves, ring 2 x 256 keys (128 KB)
