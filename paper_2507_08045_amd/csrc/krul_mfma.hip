@@ -8,7 +8,7 @@
 // registers when the cross term (the "ab" of Sec. 7's a^2 + b^2 - 2ab) is taken.
 //
 // K stream.  Per layer step the K tile arrives in NC chunks of CH keys.  Chunks are
-// copied HBM -> LDS by global_load_lds_dwordx4 (no register staging) into a ring of
+// copied HBM -> LDS by buffer_load_dwordx4 ... lds (no register staging) into a ring of
 // NBUF slots, NBUF-1 chunks ahead of the compute; one s_waitcnt + s_barrier per chunk
 // publishes a slot.  Every slot is its own LDS object and every use names its slot
 // statically, so the compiler can tell a copy in flight from the slot being read and
