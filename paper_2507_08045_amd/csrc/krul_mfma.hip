@@ -260,35 +260,38 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 }
 
                 const unsigned char *slot = slot_ptr(ring_half + c);
+                // Logits of all this wave's blocks first, the independent accumulator chains
+                // interleaved so that no MFMA waits for the one issued just before it ...
+                f32x16 acc[KBW][RB];
 #pragma unroll
-                for (int kb = 0; kb < KBW; ++kb) {
-                    const int blk = c * KBW + kb;
-                    f32x16 acc[RB];
+                for (int kb = 0; kb < KBW; ++kb)
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
-                    const unsigned char *kbp = slot + (wk * KBW + kb) * 32 * (D * 2);
-                    bf16x8 a[KS];
+                        for (int v = 0; v < 16; ++v) acc[kb][rb][v] = 0.f;
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks)
-                        a[ks] = *reinterpret_cast<const bf16x8 *>(kbp + (a_base ^ (ks << 5)));
+                for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks)
+                    for (int kb = 0; kb < KBW; ++kb) {
+                        const unsigned char *kbp = slot + (wk * KBW + kb) * 32 * (D * 2);
+                        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kbp + (a_base ^ (ks << 5)));
 #pragma unroll
                         for (int rb = 0; rb < RB; ++rb)
-                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qf[rb][ks], acc[rb], 0, 0, 0);
-                    if (c == NC - 1 && kb == KBW - 1) {
-                        // the old query rows are dead once the MFMAs above have issued; do not
-                        // let the loads below be scheduled ahead of them (they would need a
-                        // second set of registers)
-                        load_q(l + 1 == L ? 0 : l + 1);   // next step's query rows
-                        if (more) {                        // ring loads stay the youngest loads
-                            issue_chunk((ring_half + c + PF) % NBUF);
-                            n_issued = n_issued + 1;
-                        }
+                            acc[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][ks], acc[kb][rb], 0, 0, 0);
                     }
+                if (c == NC - 1) {
+                    // the old query rows are dead once the MFMAs above have issued
+                    load_q(l + 1 == L ? 0 : l + 1);   // next step's query rows
+                    if (more) {                        // ring loads stay the youngest loads
+                        issue_chunk((ring_half + c + PF) % NBUF);
+                        n_issued = n_issued + 1;
+                    }
+                }
 
+                // ... then the softmax statistics and cross terms, block by block.
+#pragma unroll
+                for (int kb = 0; kb < KBW; ++kb) {
+                    const int blk = c * KBW + kb;
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) {
                         if (ragged) {
@@ -297,11 +300,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                             asm volatile("" : "+v"(lim));   // keep the 16 compares here, not hoisted
 #pragma unroll
                             for (int v = 0; v < 16; ++v)
-                                if (8 * (v >> 2) + (v & 3) >= lim) acc[rb][v] = -INFINITY;
+                                if (8 * (v >> 2) + (v & 3) >= lim) acc[kb][rb][v] = -INFINITY;
                         }
-                        float tmax = acc[rb][0];
+                        float tmax = acc[kb][rb][0];
 #pragma unroll
-                        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[rb][v]);
+                        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[kb][rb][v]);
                         const float xm = tmax * cs;
                         if (__any(xm > mcur[rb] + kLazy)) {
                             const float mnew = fmaxf(mcur[rb], xm);
@@ -316,7 +319,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                         float bz = 0.f, bn = 0.f, bd = 0.f;
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
-                            const float ev = __builtin_amdgcn_exp2f(fmaf(acc[rb][v], cs, negm));
+                            const float ev = __builtin_amdgcn_exp2f(fmaf(acc[kb][rb][v], cs, negm));
                             bz += ev;
                             bn = fmaf(ev, ev, bn);
                             bd = fmaf(ev, e[rb][blk][v], bd);
