@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--with-dist", action="store_true",
+                    help="also ask for the Euclidean distance by-product (pair_dist)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run the library's plain copy kernel on MIB MiB a few times (a known-size "
                          "reference for rocprofv3 traffic counters)")
@@ -99,15 +101,17 @@ def main():
     out = {
         "pair_score": torch.empty((w.B, w.L - 1), dtype=torch.float32, device="cuda"),
         "head_score": torch.empty((w.B, w.L - 1, w.Hq), dtype=torch.float32, device="cuda"),
-        "pair_dist": torch.empty((w.B, w.L - 1), dtype=torch.float32, device="cuda"),
     }
+    if args.with_dist:   # the Euclidean by-product costs one more running sum per logit
+        out["pair_dist"] = torch.empty((w.B, w.L - 1), dtype=torch.float32, device="cuda")
     pairs = torch.empty((w.B, w.n_select), dtype=torch.int32, device="cuda")
     count = torch.empty((w.B,), dtype=torch.int32, device="cuda")
     K = args.steps
     evs = [(hipevents.create(), hipevents.create()) for _ in range(K)]
 
     def step(ev=None):
-        kr.pair_similarity(q, k, flags=args.flags, workspace=ws, out=out, events=ev)
+        kr.pair_similarity(q, k, flags=args.flags, workspace=ws, out=out, events=ev,
+                           want_pair_dist=args.with_dist)
         kr.select_pairs(out["pair_score"], w.n_select, out_pairs=pairs, out_count=count)
 
     for _ in range(args.warmup):
@@ -148,7 +152,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} L={w.L} Hq/Hkv={w.Hq}/{w.Hkv} d={w.d} S={w.S} Tq={w.Tq} "
-                               f"{w.dtype}, select {w.n_select} pairs", "score_elems": w.score_elems},
+                               f"{w.dtype}, select {w.n_select} pairs", "score_elems": w.score_elems,
+                   "outputs": "pair_score+head_score" + ("+pair_dist" if args.with_dist else "")},
         "roofline": {"bound": "hbm", "achieved": hbm_gbs, "peak": 8000.0, "unit": "GB/s",
                      "frac": hbm_gbs / 8000.0, "traffic": traffic,
                      "kernel": "sim_mfma_kernel" if w.dtype == "bf16" and not (args.flags & 256) else "sim_generic_kernel",

@@ -166,6 +166,7 @@ int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const v
     p.Tq = shape->n_query;
     p.keys_per_split = pl.keys_per_split;
     p.c = pl.c;
+    p.want_dist = pair_dist != nullptr;
     p.lay = pl.lay;
 
     if (event_begin && hipEventRecord(static_cast<hipEvent_t>(event_begin), st) != hipSuccess)

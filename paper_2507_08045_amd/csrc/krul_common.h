@@ -70,6 +70,7 @@ struct SimParams {
     int B, L, Hq, Hkv, g, d, S, Tq;
     int keys_per_split;
     float c;
+    int want_dist;   // the distance is asked for: Z = sum e must be accumulated too
     StateLayout lay;
 };
 
@@ -78,7 +79,7 @@ hipError_t launch_sim_generic(const SimParams &p, int dtype, int n_workgroups, h
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st);
 hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, int L, int Hq, int Hkv,
                            int Tq, float *head_cos, float *head_dist, float *pair_cos,
-                           float *pair_dist, hipStream_t st);
+                           float *pair_dist, hipStream_t st);   // pair_dist may be null
 hipError_t launch_select(const float *pair_score, const uint8_t *eligible, int batch, int n_layers,
                          int n_select, int32_t *out_pairs, int32_t *out_count, hipStream_t st);
 

@@ -52,7 +52,7 @@ __device__ inline void merge_into(RowAcc &r, float ma, float za, float na, float
 // the same g read consecutive rows, i.e. consecutive records.
 __global__ __launch_bounds__(kThreads) void finalize_heads_kernel(
     StateLayout lay, const float4 *__restrict__ state, int L, int Hq, int Hkv, int Tq, int G,
-    float *__restrict__ head_cos, float *__restrict__ head_dist)
+    int want_dist, float *__restrict__ head_cos, float *__restrict__ head_dist)
 {
     __shared__ float red[kThreads / 64];
     const int NP = L - 1;
@@ -87,9 +87,11 @@ __global__ __launch_bounds__(kThreads) void finalize_heads_kernel(
         }
         if (t < Tq && g == 0) {
             cos_acc += acc.C * rsqrtf(acc.Na * acc.Nb);
-            const float ia = 1.f / acc.Za, ib = 1.f / acc.Zb;
-            const float d2 = acc.Na * ia * ia + acc.Nb * ib * ib - 2.f * acc.C * ia * ib;
-            dist_acc += sqrtf(fmaxf(d2, 0.f));
+            if (want_dist) {   // (Z is only accumulated when the distance is asked for)
+                const float ia = 1.f / acc.Za, ib = 1.f / acc.Zb;
+                const float d2 = acc.Na * ia * ia + acc.Nb * ib * ib - 2.f * acc.C * ia * ib;
+                dist_acc += sqrtf(fmaxf(d2, 0.f));
+            }
         }
     }
     const float cs = block_sum(cos_acc, red);
@@ -126,7 +128,7 @@ hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, i
     int G = 1;
     while (G < 64 && G * Tq < kThreads && G < lay.partials) G <<= 1;
     hipLaunchKernelGGL(finalize_heads_kernel, dim3(n_pairs_total * Hq), dim3(kThreads), 0, st, lay,
-                       state, L, Hq, Hkv, Tq, G, head_cos, head_dist);
+                       state, L, Hq, Hkv, Tq, G, pair_dist != nullptr, head_cos, head_dist);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(finalize_pairs_kernel, dim3((n_pairs_total + 127) / 128), dim3(128), 0, st,

@@ -42,6 +42,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr float kLazy = 16.0f;
+constexpr float kBig = 4294967296.0f;   // 2^(2*kLazy): bound on a block's sum of squared exponentials
 
 template <int D_, int WR_, int WK_, int KBW_>
 struct Cfg {
@@ -85,7 +86,7 @@ __device__ inline int swz(int row)
     return D == 128 ? (row & 15) : ((row >> 1) & 7);
 }
 
-template <class C>
+template <class C, bool WZ>   // WZ: also accumulate Z = sum e (needed for the distance only)
 __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 {
     constexpr int D = C::D, WK = C::WK, KBW = C::KBW, NC = C::NC, KS = C::KS;
@@ -276,19 +277,15 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 for (int kb = 0; kb < KBW; ++kb) {
                     const int blk = c * KBW + kb;
                     f32x16 &x = acc[c & 1][kb];
-                    float tmax = x[0];
+                    if (blk == 0) {
+                        // first block of a step: bring the reference exponent (which starts from
+                        // "no key seen", or from the previous tile's) up to this block's maximum
+                        // before use; no sums of this step exist yet that would need rescaling
+                        float tmax = x[0];
 #pragma unroll
-                    for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, x[v]);
-                    const float xm = tmax * cs;
-                    if (__any(xm > mcur + kLazy)) {
-                        const float mnew = fmaxf(mcur, xm);
-                        const float f = __builtin_amdgcn_exp2f(mcur - mnew);
-                        tz *= f;
-                        tn *= f * f;
-                        mcur = mnew;
-                        raised = true;
+                        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, x[v]);
+                        mcur = fmaxf(mcur, tmax * cs);
                     }
-                    mb[blk] = mcur;
                     // The next chunk's logits of this block are formed while this block's
                     // exponentials are taken: independent work for the matrix and vector units.
                     acc[(c + 1) & 1][kb] = logits(nslot, kb);
@@ -303,17 +300,45 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                         __builtin_amdgcn_sched_group_barrier(0x002, 80 / KS, 0);
                         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                     }
-                    const float negm = -mcur;
+                    // Exponentials under the current reference exponent; if one of them turns out
+                    // large (above 2^kLazy, or overflowed) the exponent is raised to the block's
+                    // maximum, the running sums are rescaled, and the block is taken again.
+                    float ev[16];
                     float bz = 0.f, bn = 0.f, bd = 0.f;
+                    {
+                        const float negm = -mcur;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float ev = __builtin_amdgcn_exp2f(fmaf(x[v], cs, negm));
-                        bz += ev;
-                        bn = fmaf(ev, ev, bn);
-                        bd = fmaf(ev, e[blk][v], bd);
-                        e[blk][v] = ev;
+                        for (int v = 0; v < 16; ++v) {
+                            ev[v] = __builtin_amdgcn_exp2f(fmaf(x[v], cs, negm));
+                            if (WZ) bz += ev[v];
+                            bn = fmaf(ev[v], ev[v], bn);
+                            bd = fmaf(ev[v], e[blk][v], bd);
+                        }
                     }
                     asm volatile("" : "+v"(bz), "+v"(bn), "+v"(bd));   // the sums are taken here, beside the MFMAs
+                    if (__any(!(bn <= kBig))) {
+                        float tmax = x[0];
+#pragma unroll
+                        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, x[v]);
+                        const float mnew = fmaxf(mcur, tmax * cs);
+                        const float f = __builtin_amdgcn_exp2f(mcur - mnew);
+                        tz *= f;
+                        tn *= f * f;
+                        mcur = mnew;
+                        raised = true;
+                        const float negm = -mcur;
+                        bz = bn = bd = 0.f;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            ev[v] = __builtin_amdgcn_exp2f(fmaf(x[v], cs, negm));
+                            if (WZ) bz += ev[v];
+                            bn = fmaf(ev[v], ev[v], bn);
+                            bd = fmaf(ev[v], e[blk][v], bd);
+                        }
+                    }
+                    mb[blk] = mcur;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) e[blk][v] = ev[v];
                     tz += bz;
                     tn += bn;
                     dot[blk] = bd;
@@ -392,7 +417,10 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 template <class C>
 hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
 {
-    hipLaunchKernelGGL(sim_mfma_kernel<C>, dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
+    if (p.want_dist)
+        hipLaunchKernelGGL((sim_mfma_kernel<C, true>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
+    else
+        hipLaunchKernelGGL((sim_mfma_kernel<C, false>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
     return hipGetLastError();
 }
 
