@@ -7,7 +7,7 @@
 namespace krul {
 namespace {
 
-constexpr int kTargetWorkgroups = 512;   // eight waves' worth of workgroups on each of 256 CUs, twice
+constexpr int kTargetWorkgroups = 512;   // two eight-wave workgroups for each of 256 CUs
 constexpr size_t kAlign = 256;
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -50,12 +50,14 @@ int make_plan(const krul_shape_t *s, Plan *pl)
         int kt;
         if (Rk <= 32) { y.variant = kMfmaSlim; y.wr = 1; y.wk = 8; y.rb = 1; kt = 512; }
         else if (Rk <= 64) { y.variant = kMfmaMid; y.wr = 2; y.wk = 4; y.rb = 1; kt = 512; }
-        else { y.variant = kMfmaWide; y.wr = 4; y.wk = 1; y.rb = 1; kt = 128; }
+        else { y.variant = kMfmaWide; y.wr = 4; y.wk = 2; y.rb = 1; kt = 256; }
         const long long r_wg = y.wr * y.rb * 32;
         const long long nrt = (Rk + r_wg - 1) / r_wg;
         const long long units = B * Hkv * nrt;
         const long long tiles = (S + kt - 1) / kt;
-        long long want = (kTargetWorkgroups + units - 1) / units;
+        // the wide tile's workgroups are resident one per CU: aim for one round of them
+        const long long target = y.variant == kMfmaWide ? kTargetWorkgroups / 2 : kTargetWorkgroups;
+        long long want = (target + units - 1) / units;
         if (want < 1 || (s->flags & KRUL_FLAG_SINGLE_SPLIT)) want = 1;
         long long nsplit = want < tiles ? want : tiles;
         const long long tps = (tiles + nsplit - 1) / nsplit;

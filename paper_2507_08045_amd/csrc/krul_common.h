@@ -31,7 +31,7 @@ constexpr float kMInit = -1.0e30f;
 
 enum Variant : int {
     kGeneric = 0,   // portable VALU kernel: one wave per (row, key split)
-    kMfmaWide = 1,  // bf16 MFMA, 128 rows x 128 keys per workgroup tile (4x1 waves)
+    kMfmaWide = 1,  // bf16 MFMA, 128 rows x 256 keys per workgroup tile (4x2 waves)
     kMfmaMid = 2,   // bf16 MFMA,  64 rows x 512 keys per workgroup tile (2x4 waves)
     kMfmaSlim = 3,  // bf16 MFMA,  32 rows x 512 keys per workgroup tile (1x8 waves)
 };

@@ -428,8 +428,8 @@ hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
 
 // Tile shapes (rows x keys per workgroup tile) must match make_plan().
 //           D  WR WK KBW
-typedef Cfg<128, 4, 1, 2> Wide128;   // 128 x 128, 4 waves, ring 2 x  64 keys ( 32 KB)
-typedef Cfg<64, 4, 1, 2> Wide64;
+typedef Cfg<128, 4, 2, 2> Wide128;   // 128 x 256, 8 waves, ring 2 x 128 keys ( 64 KB)
+typedef Cfg<64, 4, 2, 2> Wide64;
 typedef Cfg<128, 2, 4, 2> Mid128;    //  64 x 512, 8 waves, ring 2 x 256 keys (128 KB)
 typedef Cfg<64, 2, 4, 2> Mid64;
 typedef Cfg<128, 1, 8, 1> Slim128;   //  32 x 512, 8 waves, ring 2 x 256 keys (128 KB)

@@ -37,6 +37,10 @@ def sampled_check(G, oracle, w, n_units, seed):
     err = np.max(np.abs(gpu_vals - hc))
     print(f"[{w.name}] {n_units} sampled units: max |gpu - oracle| = {err:.2e}", flush=True)
     assert err <= G.TOL
+    # the configuration bench.py times: cosine scores only (no distance asked for)
+    hs_c = G.gpu_scores(q, k, want_pair_dist=False)["head_score"]
+    assert np.max(np.abs(np.array([hs_c[b, l, h] for b, l, h in units]) - hc)) <= G.TOL
+    assert np.max(np.abs(hs_c - hs)) < 1e-6
     # selection: device selector == oracle selector on the same fp32 scores
     ps = torch.from_numpy(got["pair_score"]).cuda()
     pairs, count = kr.select_pairs(ps, w.n_select)
@@ -57,6 +61,12 @@ def test_c2_full(G, oracle):
     pairs, count, margin = G.check_selection(oracle, got["pair_score"], want["pair_score"], w.n_select)
     print(f"[C2 full] max err head={e1:.2e} pair={e2:.2e} dist={e3:.2e}; selected {pairs[0].tolist()}, "
           f"min score gap {margin:.2e}", flush=True)
+    # the configuration bench.py times: cosine scores only (no distance asked for)
+    got_c = G.gpu_scores(q, k, want_pair_dist=False)
+    assert got_c["pair_dist"] is None
+    G.assert_close(got_c["head_score"], want["head_score"], G.TOL, "C2 head_score (cosine only)")
+    G.assert_close(got_c["pair_score"], want["pair_score"], G.TOL, "C2 pair_score (cosine only)")
+    G.check_selection(oracle, got_c["pair_score"], want["pair_score"], w.n_select)
     # scores follow the generator's correlations: exp(rho_q*rho_k - 1) up to finite-S effects
     rho = w.rho_k[0, :, 0]
     assert np.corrcoef(rho, got["pair_score"][0])[0, 1] > 0.98

@@ -2,6 +2,7 @@
 same seeded inputs, element by element.  Similarities must agree within 2e-3
 absolute; selections must be bit-exact (see gpu_util.check_selection)."""
 import math
+import zlib
 
 import numpy as np
 import pytest
@@ -63,7 +64,7 @@ MFMA_CASES = [
 def test_bf16_mfma_small(G, oracle, case):
     import paper_2507_08045_amd as kr
     name, B, L, Hq, Hkv, d, S, Tq = case
-    rng = np.random.default_rng(abs(hash(name)) % 2**31)
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
     rho = rng.uniform(0.5, 0.95, size=(B, L - 1, Hkv))
     w = workloads.make(name, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, dtype="bf16", rho_k=rho, seed=11)
     got, _ = run_case(G, oracle, w)
@@ -72,6 +73,14 @@ def test_bf16_mfma_small(G, oracle, case):
     got2, _ = run_case(G, oracle, w, flags=kr.KRUL_FLAG_GENERIC_KERNEL)
     assert np.max(np.abs(got1["head_score"] - got["head_score"])) < 1e-4
     assert np.max(np.abs(got2["head_score"] - got["head_score"])) < 1e-4
+    # cosine only (no distance asked for: the kernel then skips the sum it alone needs)
+    for fl in (0, kr.KRUL_FLAG_SINGLE_SPLIT):
+        q, k = G.to_device(w)
+        got3 = G.gpu_scores(q, k, flags=fl, want_pair_dist=False)
+        assert got3["pair_dist"] is None
+        ref = got if fl == 0 else got1
+        assert np.max(np.abs(got3["head_score"] - ref["head_score"])) < 1e-6
+        assert np.max(np.abs(got3["pair_score"] - ref["pair_score"])) < 1e-6
 
 
 def test_identical_layers_give_one(G, oracle):
