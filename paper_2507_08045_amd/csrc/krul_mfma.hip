@@ -44,10 +44,11 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr float kLazy = 16.0f;
 constexpr float kBig = 4294967296.0f;   // 2^(2*kLazy): bound on a block's sum of squared exponentials
 
-template <int D_, int WR_, int WK_, int KBW_>
+template <int D_, int WR_, int WK_, int KBW_, int NC_>
 struct Cfg {
     static constexpr int D = D_, WR = WR_, WK = WK_, KBW = KBW_;
-    static constexpr int NC = 2;                   // chunks per key tile = ring slots
+    static constexpr int NC = NC_;                 // chunks per key tile = ring slots
+    static constexpr int PF = NC - 1;              // chunks in flight ahead of the MFMAs
     static constexpr int NW = WR * WK;
     static constexpr int THREADS = NW * 64;
     static constexpr int R_WG = WR * 32;           // query rows per workgroup
@@ -65,6 +66,8 @@ struct Cfg {
     static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
     static_assert(CH * PPR % THREADS == 0, "chunk must split evenly over threads");
     static_assert(D == 64 || D == 128, "head_dim 64 or 128");
+    static_assert(NC == 2 || NC == 4, "two or four chunks per tile");
+    static_assert(NC == 2 || WK * QPW == NQI, "every wave must issue the same number of copies");
 };
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8]).
@@ -90,15 +93,19 @@ template <class C, bool WZ>   // WZ: also accumulate Z = sum e (needed for the d
 __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 {
     constexpr int D = C::D, WK = C::WK, KBW = C::KBW, NC = C::NC, KS = C::KS;
-    constexpr int NLD = C::NLD, PPR = C::PPR, NBLK = C::NBLK, RPI = C::RPI;
+    constexpr int NLD = C::NLD, PPR = C::PPR, NBLK = C::NBLK, RPI = C::RPI, PF = C::PF;
     __shared__ __attribute__((aligned(1024))) unsigned char ring0[C::SLOT_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char ring1[C::SLOT_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char ring2[NC > 2 ? C::SLOT_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char ring3[NC > 2 ? C::SLOT_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char qlds[C::WR * C::QBYTES];
     __shared__ float red[C::NW][4][32];
     auto slot_ptr = [&](int i) __attribute__((always_inline)) -> unsigned char * {
         switch (i) {   // i is a constant at every call site once the loops are unrolled
         case 0: return ring0;
-        default: return ring1;
+        case 1: return ring1;
+        case 2: return ring2;
+        default: return ring3;
         }
     };
 
@@ -222,11 +229,12 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 #pragma unroll
         for (int v = 0; v < 16; ++v) e[c][v] = 0.f;
 
-    // ---- prologue: query rows of layer 0 and the first two chunks; logits of chunk 0
+    // ---- prologue: query rows of layer 0 and the first NC chunks (there are at least 2*NC);
+    // logits of chunk 0
     issue_q(0, true);
-    issue_chunk(0, true);
-    issue_chunk(1, true);
-    __builtin_amdgcn_s_waitcnt(wait_vm(NLD));   // all but chunk 1 (loads return in order)
+#pragma unroll
+    for (int i = 0; i < NC; ++i) issue_chunk(i, true);
+    __builtin_amdgcn_s_waitcnt(wait_vm(PF * NLD));   // all but the chunks after chunk 0 (loads return in order)
     __builtin_amdgcn_s_barrier();
     read_q();
     f32x16 acc[2][KBW];
@@ -242,23 +250,42 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
     int ich = 0;    // chunk whose softmax statistics are taken next
     int step = 0;   // layer steps done
+    // running record of the coming step (its previous tile's), fetched one step ahead
+    float4 rec_pre = make_float4(kMInit, 0.f, 0.f, 0.f);
     for (int tile = 0; tile < ntiles; ++tile) {
         const int tile_key0 = key_begin + tile * C::KT;
         const bool ragged = tile_key0 + C::KT > key_end;
         const bool last_tile = tile == ntiles - 1;
 
         for (int l = 0; l < L; ++l, ++step) {
-            float4 rec = tile > 0 ? spill[spill_index(l)] : make_float4(kMInit, 0.f, 0.f, 0.f);
+            const float4 rec = rec_pre;
             float mcur = rec.x, tz = 0.f, tn = 0.f;
             float mb[NBLK], dot[NBLK];   // per block: exponent used, dot with previous layer
             bool raised = false;         // some lane raised m during this step (wave-uniform)
 #pragma unroll
             for (int c = 0; c < NC; ++c, ++ich) {
-                // Chunk ich+1 (copied one chunk ago) and, before the last chunk of a step, the
+                // Chunk ich+1 (copied PF chunks ago) and, before the last chunk of a step, the
                 // next layer's query rows must have landed; past the barrier every wave has
-                // finished reading chunk ich from its slot, which is then refilled.
-                __builtin_amdgcn_s_waitcnt(wait_vm(0));
+                // finished reading chunk ich from its slot, which is then refilled.  Loads
+                // return in order: it is enough that no more are outstanding than were issued
+                // after the ones needed -- the copies of the PF-1 chunks issued since, and, in
+                // the chunks between a step's first and last, the copies of the query rows
+                // (issued during the first, needed at the last).  Record stores in flight only
+                // make this wait a little longer than needed.
+                if (c != 0 && c != NC - 1)
+                    __builtin_amdgcn_s_waitcnt(wait_vm((PF - 1) * NLD + C::QPW));
+                else
+                    __builtin_amdgcn_s_waitcnt(wait_vm((PF - 1) * NLD));
                 __builtin_amdgcn_s_barrier();
+                if (c == 0) {
+                    // The next step's running record was written L-1 steps ago (by this lane).
+                    const int ln = l + 1 == L ? 0 : l + 1;
+                    rec_pre = make_float4(kMInit, 0.f, 0.f, 0.f);
+                    if ((l + 1 == L ? tile + 1 : tile) > 0 && step + 1 < nsteps) {
+                        if (L < 4) __builtin_amdgcn_s_waitcnt(wait_vm(0));   // (then it may still be on its way)
+                        rec_pre = spill[spill_index(ln)];
+                    }
+                }
                 if (c == NC - 1) read_q();   // every wave has the old rows in use no more
                 const unsigned char *nslot = slot_ptr((c + 1) % NC);
 
@@ -288,33 +315,47 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                     }
                     // The next chunk's logits of this block are formed while this block's
                     // exponentials are taken: independent work for the matrix and vector units.
-                    acc[(c + 1) & 1][kb] = logits(nslot, kb);
-                    // the copies of this iteration are issued in between as well: chunk ich+2
-                    // into the slot chunk ich was read from, the next step's query rows
-                    if (kb == 0) issue_chunk(c, ich + 2 < nchunks);
-                    if (c == 0 && kb == KBW - 1) issue_q(l + 1 == L ? 0 : l + 1, step + 1 < nsteps);
+                    // All operands are read up front, so that no MFMA waits for LDS; the copies of
+                    // this iteration are issued here as well: chunk ich+1+PF into the slot chunk
+                    // ich was read from, the next step's query rows.
+                    bf16x8 aop[KS];
+                    {
+                        const unsigned char *kbp = nslot + (wk * KBW + kb) * 32 * (D * 2);
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {   // issue order: one MFMA, then a share of the vector work
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 80 / KS, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                        for (int ks = 0; ks < KS; ++ks)
+                            aop[ks] = *reinterpret_cast<const bf16x8 *>(kbp + (a_base ^ (ks << 5)));
                     }
+                    if (kb == 0) issue_chunk(c, ich + 1 + PF < nchunks);
+                    if (c == 0 && kb == KBW - 1) issue_q(l + 1 == L ? 0 : l + 1, step + 1 < nsteps);
                     // Exponentials under the current reference exponent; if one of them turns out
                     // large (above 2^kLazy, or overflowed) the exponent is raised to the block's
                     // maximum, the running sums are rescaled, and the block is taken again.
+                    // One MFMA, then the vector work of 16/KS logits, and so on: the empty asm
+                    // statements keep that order (the compiler would issue the MFMAs back to back,
+                    // each waiting for the one before, and the vector work after them).
+                    f32x16 nx;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) nx[v] = 0.f;
                     float ev[16];
                     float bz = 0.f, bn = 0.f, bd = 0.f;
                     {
                         const float negm = -mcur;
+                        constexpr int VPK = 16 / KS;
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            ev[v] = __builtin_amdgcn_exp2f(fmaf(x[v], cs, negm));
-                            if (WZ) bz += ev[v];
-                            bn = fmaf(ev[v], ev[v], bn);
-                            bd = fmaf(ev[v], e[blk][v], bd);
+                        for (int ks = 0; ks < KS; ++ks) {
+                            nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], qf[ks], nx, 0, 0, 0);
+                            asm volatile("" : "+v"(nx));
+#pragma unroll
+                            for (int v = ks * VPK; v < (ks + 1) * VPK; ++v) {
+                                ev[v] = __builtin_amdgcn_exp2f(fmaf(x[v], cs, negm));
+                                if (WZ) bz += ev[v];
+                                bn = fmaf(ev[v], ev[v], bn);
+                                bd = fmaf(ev[v], e[blk][v], bd);
+                            }
+                            if (ks + 1 < KS) asm volatile("" : "+v"(bz), "+v"(bn), "+v"(bd));
                         }
                     }
+                    acc[(c + 1) & 1][kb] = nx;
                     asm volatile("" : "+v"(bz), "+v"(bn), "+v"(bd));   // the sums are taken here, beside the MFMAs
                     if (__any(!(bn <= kBig))) {
                         float tmax = x[0];
@@ -427,13 +468,13 @@ hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
 }  // namespace
 
 // Tile shapes (rows x keys per workgroup tile) must match make_plan().
-//           D  WR WK KBW
-typedef Cfg<128, 4, 2, 2> Wide128;   // 128 x 256, 8 waves, ring 2 x 128 keys ( 64 KB)
-typedef Cfg<64, 4, 2, 2> Wide64;
-typedef Cfg<128, 2, 4, 2> Mid128;    //  64 x 512, 8 waves, ring 2 x 256 keys (128 KB)
-typedef Cfg<64, 2, 4, 2> Mid64;
-typedef Cfg<128, 1, 8, 1> Slim128;   //  32 x 512, 8 waves, ring 2 x 256 keys (128 KB)
-typedef Cfg<64, 1, 8, 1> Slim64;
+//           D  WR WK KBW NC
+typedef Cfg<128, 4, 2, 1, 4> Wide128;   // 128 x 256, 8 waves, ring 4 x  64 keys ( 64 KB)
+typedef Cfg<64, 4, 2, 1, 4> Wide64;
+typedef Cfg<128, 2, 4, 1, 4> Mid128;    //  64 x 512, 8 waves, ring 4 x 128 keys (128 KB)
+typedef Cfg<64, 2, 4, 1, 4> Mid64;
+typedef Cfg<128, 1, 8, 1, 2> Slim128;   //  32 x 512, 8 waves, ring 2 x 256 keys (128 KB)
+typedef Cfg<64, 1, 8, 1, 2> Slim64;
 
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
 {
