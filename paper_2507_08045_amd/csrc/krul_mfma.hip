@@ -72,6 +72,7 @@ struct Cfg {
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8]).
 constexpr int wait_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+constexpr int wait_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0070; }   // ... and lgkmcnt(0)
 constexpr int kWaitLgkm0 = 0xC07F;
 
 // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
@@ -242,7 +243,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     for (int kb = 0; kb < KBW; ++kb) acc[0][kb] = logits(slot_ptr(0), kb);
 
     const float cs = p.c;
-    float f_prev = 1.f, mrg_prev = 1.f;
+    float f_prev = 1.f;
     float sprev[NBLK];    // previous layer step: 2^(block exponent - final exponent)
     bool raised_prev = false;
 #pragma unroll
@@ -250,6 +251,55 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
     int ich = 0;    // chunk whose softmax statistics are taken next
     int step = 0;   // layer steps done
+    float mrg_prev = 1.f;   // this lane's factor onto the merged exponent, previous layer
+    // The partials of a row (two half-waves, WK waves) are merged in two phases that ride on
+    // the chunk barriers of the following step, so that the merge costs no barrier of its own:
+    // at the end of a step every wave posts its exponent; after the next barrier (phase B) all
+    // take the common exponent, rescale and post their sums; after the barrier after that
+    // (phase C) one wave per wave row adds them up and stores the record.
+    float4 mg_out = make_float4(0.f, 0.f, 0.f, 0.f);
+    float mg_m = 0.f, mg_z = 0.f, mg_n = 0.f, mg_c = 0.f;
+    int mg_l = 0;
+    bool mg_b = false, mg_c_on = false;   // phases pending (uniform over the workgroup)
+    auto merge_phase_b = [&]() __attribute__((always_inline)) {
+        float M = mg_m;
+        if (WK > 1) {
+            M = red[wr * WK][0][l32];
+#pragma unroll
+            for (int w2 = 1; w2 < WK; ++w2) M = fmaxf(M, red[wr * WK + w2][0][l32]);
+        }
+        const float f = __builtin_amdgcn_exp2f(mg_out.x - M);
+        const float z = mg_out.y * f, nn = mg_out.z * f * f, cc = mg_out.w * f * mrg_prev;
+        mrg_prev = f;
+        mg_m = M;
+        mg_z = z + __shfl_xor(z, 32, 64);
+        mg_n = nn + __shfl_xor(nn, 32, 64);
+        mg_c = cc + __shfl_xor(cc, 32, 64);
+        if (WK > 1) {
+            red[wave][1][l32] = mg_z;   // both half-waves hold the same sums
+            red[wave][2][l32] = mg_n;
+            red[wave][3][l32] = mg_c;
+            mg_c_on = true;
+        } else {
+            const size_t idx = ((size_t)wg * L + mg_l) * C::R_WG + wr * 32 + l32;
+            p.state[idx] = make_float4(mg_m, mg_z, mg_n, mg_c);
+        }
+        mg_b = false;
+    };
+    auto merge_phase_c = [&]() __attribute__((always_inline)) {
+        float zs = 0.f, ns = 0.f, cc2 = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < WK; ++w2) {
+            zs += red[wr * WK + w2][1][l32];
+            ns += red[wr * WK + w2][2][l32];
+            cc2 += red[wr * WK + w2][3][l32];
+        }
+        if (wk == 0) {   // wave-uniform; lanes l and l+32 store the same record
+            const size_t idx = ((size_t)wg * L + mg_l) * C::R_WG + wr * 32 + l32;
+            p.state[idx] = make_float4(mg_m, zs, ns, cc2);
+        }
+        mg_c_on = false;
+    };
     // running record of the coming step (its previous tile's), fetched one step ahead
     float4 rec_pre = make_float4(kMInit, 0.f, 0.f, 0.f);
     for (int tile = 0; tile < ntiles; ++tile) {
@@ -273,10 +323,12 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 // (issued during the first, needed at the last).  Record stores in flight only
                 // make this wait a little longer than needed.
                 if (c != 0 && c != NC - 1)
-                    __builtin_amdgcn_s_waitcnt(wait_vm((PF - 1) * NLD + C::QPW));
+                    __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0((PF - 1) * NLD + C::QPW));
                 else
-                    __builtin_amdgcn_s_waitcnt(wait_vm((PF - 1) * NLD));
+                    __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0((PF - 1) * NLD));
                 __builtin_amdgcn_s_barrier();
+                if (c == 0 && mg_b) merge_phase_b();
+                if (c == 1 && mg_c_on) merge_phase_c();
                 if (c == 0) {
                     // The next step's running record was written L-1 steps ago (by this lane).
                     const int ln = l + 1 == L ? 0 : l + 1;
@@ -415,43 +467,25 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
             if (!last_tile) {
                 spill[spill_index(l)] = out;
             } else {
-                // ---- merge the 2*WK partials of each row: common exponent, then sums
-                float M = fmaxf(out.x, __shfl_xor(out.x, 32, 64));
-                if (WK > 1) {
-                    red[wave][0][l32] = M;   // both half-waves hold the same value
-                    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
-                    __builtin_amdgcn_s_barrier();
-                    M = red[wr * WK][0][l32];
-#pragma unroll
-                    for (int w2 = 1; w2 < WK; ++w2) M = fmaxf(M, red[wr * WK + w2][0][l32]);
-                }
-                const float f = __builtin_amdgcn_exp2f(out.x - M);
-                float z = out.y * f, nn = out.z * f * f, cc = out.w * f * mrg_prev;
-                mrg_prev = f;
-                float zs = z + __shfl_xor(z, 32, 64);
-                float ns = nn + __shfl_xor(nn, 32, 64);
-                float cc2 = cc + __shfl_xor(cc, 32, 64);
-                if (WK > 1) {
-                    red[wave][1][l32] = zs;   // both half-waves hold the same sums
-                    red[wave][2][l32] = ns;
-                    red[wave][3][l32] = cc2;
-                    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
-                    __builtin_amdgcn_s_barrier();
-                    zs = ns = cc2 = 0.f;
-#pragma unroll
-                    for (int w2 = 0; w2 < WK; ++w2) {
-                        zs += red[wr * WK + w2][1][l32];
-                        ns += red[wr * WK + w2][2][l32];
-                        cc2 += red[wr * WK + w2][3][l32];
-                    }
-                    // red is next written after the following layer step's chunk barriers
-                }
-                if (wk == 0) {   // wave-uniform; lanes l and l+32 store the same record
-                    const size_t idx = ((size_t)wg * L + l) * C::R_WG + wr * 32 + l32;
-                    p.state[idx] = make_float4(M, zs, ns, cc2);
-                }
+                // ---- post this lane pair's exponent; the merge follows during the next step
+                mg_out = out;
+                mg_m = fmaxf(out.x, __shfl_xor(out.x, 32, 64));
+                mg_l = l;
+                if (WK > 1) red[wave][0][l32] = mg_m;   // both half-waves hold the same value
+                mg_b = true;
             }
         }
+    }
+    // the last step's merge
+    if (mg_b) {
+        __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+        __builtin_amdgcn_s_barrier();
+        merge_phase_b();
+    }
+    if (mg_c_on) {
+        __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+        __builtin_amdgcn_s_barrier();
+        merge_phase_c();
     }
 }
 
