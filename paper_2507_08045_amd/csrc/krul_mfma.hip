@@ -95,10 +95,12 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 {
     constexpr int D = C::D, WK = C::WK, KBW = C::KBW, NC = C::NC, KS = C::KS;
     constexpr int NLD = C::NLD, PPR = C::PPR, NBLK = C::NBLK, RPI = C::RPI, PF = C::PF;
-    __shared__ __attribute__((aligned(1024))) unsigned char ring0[C::SLOT_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char ring1[C::SLOT_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char ring2[NC > 2 ? C::SLOT_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) unsigned char ring3[NC > 2 ? C::SLOT_BYTES : 16];
+    // (the larger alignment puts the ring first in the workgroup's LDS, within reach of the
+    // 16-bit offset field of the operand reads)
+    __shared__ __attribute__((aligned(16384))) unsigned char ring0[C::SLOT_BYTES];
+    __shared__ __attribute__((aligned(16384))) unsigned char ring1[C::SLOT_BYTES];
+    __shared__ __attribute__((aligned(16384))) unsigned char ring2[NC > 2 ? C::SLOT_BYTES : 16];
+    __shared__ __attribute__((aligned(16384))) unsigned char ring3[NC > 2 ? C::SLOT_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char qlds[C::WR * C::QBYTES];
     __shared__ float red[C::NW][4][32];
     auto slot_ptr = [&](int i) __attribute__((always_inline)) -> unsigned char * {
@@ -200,6 +202,9 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     // LDS read offset of this lane inside a 32-row block: row l32, piece (2*ks + half) ^ swz
     // = l32*(D*2) + (((2*ks) ^ a_hs) << 4) = a_base ^ (ks << 5), a_hs = half ^ swz(l32)
     const int a_base = l32 * (D * 2) + ((half ^ swz<D>(l32)) << 4);
+    // ... and the same inside this wave's first 32-key block of a chunk (a whole number of
+    // 32-row blocks further on: the bits the k-step toggles are not touched)
+    const int ka_base = a_base + wk * KBW * 32 * (D * 2);
 
     bf16x8 qf[KS];
     auto read_q = [&]() __attribute__((always_inline)) {
@@ -209,14 +214,14 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     };
     // logits of 32-key block kb of the chunk in `slot` for this lane's query row
     auto logits = [&](const unsigned char *slot, int kb) __attribute__((always_inline)) -> f32x16 {
-        const unsigned char *kbp = slot + (wk * KBW + kb) * 32 * (D * 2);
+        const unsigned char *kbp = slot + kb * 32 * (D * 2);
         f32x16 a;
 #pragma unroll
         for (int v = 0; v < 16; ++v) a[v] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                *reinterpret_cast<const bf16x8 *>(kbp + (a_base ^ (ks << 5))), qf[ks], a, 0, 0, 0);
+                *reinterpret_cast<const bf16x8 *>(kbp + (ka_base ^ (ks << 5))), qf[ks], a, 0, 0, 0);
         return a;
     };
 
@@ -372,10 +377,10 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                     // ich was read from, the next step's query rows.
                     bf16x8 aop[KS];
                     {
-                        const unsigned char *kbp = nslot + (wk * KBW + kb) * 32 * (D * 2);
+                        const unsigned char *kbp = nslot + kb * 32 * (D * 2);
 #pragma unroll
                         for (int ks = 0; ks < KS; ++ks)
-                            aop[ks] = *reinterpret_cast<const bf16x8 *>(kbp + (a_base ^ (ks << 5)));
+                            aop[ks] = *reinterpret_cast<const bf16x8 *>(kbp + (ka_base ^ (ks << 5)));
                     }
                     if (kb == 0) issue_chunk(c, ich + 1 + PF < nchunks);
                     if (c == 0 && kb == KBW - 1) issue_q(l + 1 == L ? 0 : l + 1, step + 1 < nsteps);
