@@ -102,7 +102,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     __shared__ __attribute__((aligned(16384))) unsigned char ring2[NC > 2 ? C::SLOT_BYTES : 16];
     __shared__ __attribute__((aligned(16384))) unsigned char ring3[NC > 2 ? C::SLOT_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char qlds[C::WR * C::QBYTES];
-    __shared__ float red[C::NW][4][32];
+    __shared__ float4 part[C::NW][64];   // every lane's record of the last step (m, Z, N2, C)
     auto slot_ptr = [&](int i) __attribute__((always_inline)) -> unsigned char * {
         switch (i) {   // i is a constant at every call site once the loops are unrolled
         case 0: return ring0;
@@ -256,54 +256,35 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
     int ich = 0;    // chunk whose softmax statistics are taken next
     int step = 0;   // layer steps done
-    float mrg_prev = 1.f;   // this lane's factor onto the merged exponent, previous layer
-    // The partials of a row (two half-waves, WK waves) are merged in two phases that ride on
-    // the chunk barriers of the following step, so that the merge costs no barrier of its own:
-    // at the end of a step every wave posts its exponent; after the next barrier (phase B) all
-    // take the common exponent, rescale and post their sums; after the barrier after that
-    // (phase C) one wave per wave row adds them up and stores the record.
-    float4 mg_out = make_float4(0.f, 0.f, 0.f, 0.f);
-    float mg_m = 0.f, mg_z = 0.f, mg_n = 0.f, mg_c = 0.f;
+    // The 2*WK partials of a row (two half-waves, WK waves) are merged one step late, so that
+    // the merge costs no barrier of its own: at the end of a step every lane posts its record
+    // in LDS; after the next chunk barrier the first wave of each wave row brings the partials
+    // of its rows onto their common exponent, adds them in a fixed order and stores the row
+    // records.  The cross term of partial p carries the exponents of two layers: gprev[p] is
+    // the factor that took p's exponent of the previous layer onto that layer's merged one.
+    float gprev[2 * WK];
+#pragma unroll
+    for (int pi = 0; pi < 2 * WK; ++pi) gprev[pi] = 1.f;
     int mg_l = 0;
-    bool mg_b = false, mg_c_on = false;   // phases pending (uniform over the workgroup)
-    auto merge_phase_b = [&]() __attribute__((always_inline)) {
-        float M = mg_m;
-        if (WK > 1) {
-            M = red[wr * WK][0][l32];
+    bool mg_on = false;   // a merge is pending (uniform over the workgroup)
+    auto merge_rows = [&]() __attribute__((always_inline)) {
+        float4 pp[2 * WK];
 #pragma unroll
-            for (int w2 = 1; w2 < WK; ++w2) M = fmaxf(M, red[wr * WK + w2][0][l32]);
-        }
-        const float f = __builtin_amdgcn_exp2f(mg_out.x - M);
-        const float z = mg_out.y * f, nn = mg_out.z * f * f, cc = mg_out.w * f * mrg_prev;
-        mrg_prev = f;
-        mg_m = M;
-        mg_z = z + __shfl_xor(z, 32, 64);
-        mg_n = nn + __shfl_xor(nn, 32, 64);
-        mg_c = cc + __shfl_xor(cc, 32, 64);
-        if (WK > 1) {
-            red[wave][1][l32] = mg_z;   // both half-waves hold the same sums
-            red[wave][2][l32] = mg_n;
-            red[wave][3][l32] = mg_c;
-            mg_c_on = true;
-        } else {
-            const size_t idx = ((size_t)wg * L + mg_l) * C::R_WG + wr * 32 + l32;
-            p.state[idx] = make_float4(mg_m, mg_z, mg_n, mg_c);
-        }
-        mg_b = false;
-    };
-    auto merge_phase_c = [&]() __attribute__((always_inline)) {
-        float zs = 0.f, ns = 0.f, cc2 = 0.f;
+        for (int pi = 0; pi < 2 * WK; ++pi) pp[pi] = part[wr * WK + (pi >> 1)][(pi & 1) * 32 + l32];
+        float M = pp[0].x;
 #pragma unroll
-        for (int w2 = 0; w2 < WK; ++w2) {
-            zs += red[wr * WK + w2][1][l32];
-            ns += red[wr * WK + w2][2][l32];
-            cc2 += red[wr * WK + w2][3][l32];
+        for (int pi = 1; pi < 2 * WK; ++pi) M = fmaxf(M, pp[pi].x);
+        float zs = 0.f, ns = 0.f, cc = 0.f;
+#pragma unroll
+        for (int pi = 0; pi < 2 * WK; ++pi) {
+            const float f = __builtin_amdgcn_exp2f(pp[pi].x - M);
+            zs = fmaf(pp[pi].y, f, zs);
+            ns = fmaf(pp[pi].z, f * f, ns);
+            cc = fmaf(pp[pi].w, f * gprev[pi], cc);
+            gprev[pi] = f;
         }
-        if (wk == 0) {   // wave-uniform; lanes l and l+32 store the same record
-            const size_t idx = ((size_t)wg * L + mg_l) * C::R_WG + wr * 32 + l32;
-            p.state[idx] = make_float4(mg_m, zs, ns, cc2);
-        }
-        mg_c_on = false;
+        // lanes l and l+32 hold, and store, the same record
+        p.state[((size_t)wg * L + mg_l) * C::R_WG + wr * 32 + l32] = make_float4(M, zs, ns, cc);
     };
     // running record of the coming step (its previous tile's), fetched one step ahead
     float4 rec_pre = make_float4(kMInit, 0.f, 0.f, 0.f);
@@ -332,8 +313,10 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 else
                     __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0((PF - 1) * NLD));
                 __builtin_amdgcn_s_barrier();
-                if (c == 0 && mg_b) merge_phase_b();
-                if (c == 1 && mg_c_on) merge_phase_c();
+                if (c == 0 && mg_on) {
+                    if (wk == 0) merge_rows();
+                    mg_on = false;
+                }
                 if (c == 0) {
                     // The next step's running record was written L-1 steps ago (by this lane).
                     const int ln = l + 1 == L ? 0 : l + 1;
@@ -472,25 +455,18 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
             if (!last_tile) {
                 spill[spill_index(l)] = out;
             } else {
-                // ---- post this lane pair's exponent; the merge follows during the next step
-                mg_out = out;
-                mg_m = fmaxf(out.x, __shfl_xor(out.x, 32, 64));
+                // ---- post this lane's record; the merge follows during the next step
+                part[wave][lane] = out;
                 mg_l = l;
-                if (WK > 1) red[wave][0][l32] = mg_m;   // both half-waves hold the same value
-                mg_b = true;
+                mg_on = true;
             }
         }
     }
     // the last step's merge
-    if (mg_b) {
+    if (mg_on) {
         __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
         __builtin_amdgcn_s_barrier();
-        merge_phase_b();
-    }
-    if (mg_c_on) {
-        __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
-        __builtin_amdgcn_s_barrier();
-        merge_phase_c();
+        if (wk == 0) merge_rows();
     }
 }
 
