@@ -145,31 +145,25 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     // K ring: wave-instruction j of this wave fills granules [(wave*NLD+j)*64, +64) of a slot.
     const int ld_row0 = wave * NLD * RPI + lane / PPR;
     const unsigned ld_off0 = (unsigned)(ld_row0 * (D * 2) + (((lane % PPR) ^ swz<D>(ld_row0)) * 16));
-    int pf_tile = 0, pf_l = 0, pf_c = 0;   // next chunk to fetch
-    auto issue_chunk = [&](int slot, bool live) __attribute__((always_inline)) {
-        unsigned char *dst = slot_ptr(slot);
-        const int key0 = key_begin + pf_tile * C::KT + pf_c * C::CH;
+    // The chunk copied during chunk c of a step is chunk c of the NEXT step (PF + 1 = NC chunks
+    // later), so per step one base address serves all its copies: that of the next step's
+    // layer and key tile (fetch_k), with the tile's first key (fetch_key0).
+    const uint16_t *fetch_k = kbase + (size_t)key_begin * D;
+    int fetch_key0 = key_begin;
+    auto issue_chunk = [&](int c, bool live) __attribute__((always_inline)) {
+        unsigned char *dst = slot_ptr(c);
+        const int key0 = fetch_key0 + c * C::CH;
         // Buffer addressing: a scalar descriptor for the rest of this layer's keys (rows past
         // the last key are out of range and are not fetched), one 32-bit offset per lane.
-        const uint16_t *src = kbase + (size_t)pf_l * k_layer_stride + (size_t)key0 * D;
         // (a chunk past the end of the split gets an empty range: nothing is fetched)
         const unsigned bytes = live ? (unsigned)max(S - key0, 0) * (unsigned)(D * 2) : 0u;
-        const __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(src), 0, (int)bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(fetch_k + c * (C::CH * D)), 0, (int)bytes, 0x00020000);
 #pragma unroll
         for (int j = 0; j < NLD; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rsrc, (__attribute__((address_space(3))) void *)(dst + (wave * NLD + j) * 1024), 16,
                 (int)(ld_off0 ^ xj(j)), j * 1024, 0, 0);
-        pf_c = pf_c + 1;
-        if (pf_c == NC) {
-            pf_c = 0;
-            pf_l = pf_l + 1;
-            if (pf_l == L) {
-                pf_l = 0;
-                pf_tile = pf_tile + 1;
-            }
-        }
     };
 
     // Query rows: the 32 rows of wave row wr are staged in LDS (laid out like a 32-key block)
@@ -185,9 +179,10 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                                    (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a));
     }
     const unsigned q_off0 = (unsigned)((lane / PPR) * (D * 2) + (((lane % PPR) ^ swz<D>(lane / PPR)) * 16));
-    auto issue_q = [&](int l, bool live) __attribute__((always_inline)) {
+    const uint16_t *fetch_q = qbase;   // query rows of the next step's layer
+    auto issue_q = [&](bool live) __attribute__((always_inline)) {
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint16_t *>(qbase + (size_t)l * q_layer_stride), 0, __builtin_amdgcn_readfirstlane(live ? q_rows * (D * 2) : 0), 0x00020000);
+            const_cast<uint16_t *>(fetch_q), 0, __builtin_amdgcn_readfirstlane(live ? q_rows * (D * 2) : 0), 0x00020000);
         unsigned char *dst = qlds + wr * C::QBYTES;
 #pragma unroll
         for (int jj = 0; jj < C::QPW; ++jj) {
@@ -237,7 +232,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
     // ---- prologue: query rows of layer 0 and the first NC chunks (there are at least 2*NC);
     // logits of chunk 0
-    issue_q(0, true);
+    issue_q(true);
 #pragma unroll
     for (int i = 0; i < NC; ++i) issue_chunk(i, true);
     __builtin_amdgcn_s_waitcnt(wait_vm(PF * NLD));   // all but the chunks after chunk 0 (loads return in order)
@@ -254,7 +249,6 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 #pragma unroll
     for (int k2 = 0; k2 < NBLK; ++k2) sprev[k2] = 1.f;
 
-    int ich = 0;    // chunk whose softmax statistics are taken next
     int step = 0;   // layer steps done
     // The 2*WK partials of a row (two half-waves, WK waves) are merged one step late, so that
     // the merge costs no barrier of its own: at the end of a step every lane posts its record
@@ -295,14 +289,21 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
         for (int l = 0; l < L; ++l, ++step) {
             const float4 rec = rec_pre;
+            // the step after this one: its layer and tile, and where its keys and query rows are
+            const bool has_next = step + 1 < nsteps;
+            const int ln = l + 1 == L ? 0 : l + 1;
+            const int tn_ = l + 1 == L ? tile + 1 : tile;
+            fetch_key0 = key_begin + tn_ * C::KT;
+            fetch_k = kbase + (size_t)ln * k_layer_stride + (size_t)fetch_key0 * D;
+            fetch_q = qbase + (size_t)ln * q_layer_stride;
             float mcur = rec.x, tz = 0.f, tn = 0.f;
             float mb[NBLK], dot[NBLK];   // per block: exponent used, dot with previous layer
             bool raised = false;         // some lane raised m during this step (wave-uniform)
 #pragma unroll
-            for (int c = 0; c < NC; ++c, ++ich) {
-                // Chunk ich+1 (copied PF chunks ago) and, before the last chunk of a step, the
-                // next layer's query rows must have landed; past the barrier every wave has
-                // finished reading chunk ich from its slot, which is then refilled.  Loads
+            for (int c = 0; c < NC; ++c) {
+                // The chunk after this one (copied PF chunks ago) and, before the last chunk of a
+                // step, the next layer's query rows must have landed; past the barrier every wave
+                // has finished reading this chunk from its slot, which is then refilled.  Loads
                 // return in order: it is enough that no more are outstanding than were issued
                 // after the ones needed -- the copies of the PF-1 chunks issued since, and, in
                 // the chunks between a step's first and last, the copies of the query rows
@@ -319,9 +320,8 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 }
                 if (c == 0) {
                     // The next step's running record was written L-1 steps ago (by this lane).
-                    const int ln = l + 1 == L ? 0 : l + 1;
                     rec_pre = make_float4(kMInit, 0.f, 0.f, 0.f);
-                    if ((l + 1 == L ? tile + 1 : tile) > 0 && step + 1 < nsteps) {
+                    if (tn_ > 0 && has_next) {
                         if (L < 4) __builtin_amdgcn_s_waitcnt(wait_vm(0));   // (then it may still be on its way)
                         rec_pre = spill[spill_index(ln)];
                     }
@@ -356,8 +356,8 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                     // The next chunk's logits of this block are formed while this block's
                     // exponentials are taken: independent work for the matrix and vector units.
                     // All operands are read up front, so that no MFMA waits for LDS; the copies of
-                    // this iteration are issued here as well: chunk ich+1+PF into the slot chunk
-                    // ich was read from, the next step's query rows.
+                    // this iteration are issued here as well: the next step's chunk c into the slot
+                    // this chunk was read from, the next step's query rows.
                     bf16x8 aop[KS];
                     {
                         const unsigned char *kbp = nslot + kb * 32 * (D * 2);
@@ -365,8 +365,8 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                         for (int ks = 0; ks < KS; ++ks)
                             aop[ks] = *reinterpret_cast<const bf16x8 *>(kbp + (ka_base ^ (ks << 5)));
                     }
-                    if (kb == 0) issue_chunk(c, ich + 1 + PF < nchunks);
-                    if (c == 0 && kb == KBW - 1) issue_q(l + 1 == L ? 0 : l + 1, step + 1 < nsteps);
+                    if (kb == 0) issue_chunk(c, has_next);
+                    if (c == 0 && kb == KBW - 1) issue_q(has_next);
                     // Exponentials under the current reference exponent; if one of them turns out
                     // large (above 2^kLazy, or overflowed) the exponent is raised to the block's
                     // maximum, the running sums are rescaled, and the block is taken again.
