@@ -98,6 +98,28 @@ int krul_pair_similarity(const krul_shape_t *shape, const void *q, const void *k
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * krul_pair_similarity together with the Initial-Recent (I-R) layer test that precedes it in
+ * Alg. 1 (first loop; Sec. 4.2, "Non-I-R Layer Extraction"), in the same pass over K.  With
+ * T_initial = the first 10 % and T_recent = the last 10 % of the history -- keys
+ * [0, floor(0.1 S)) and [floor(0.9 S), S) --
+ *     ir_mass[b][l]  = mean over query heads and query rows of the softmax mass on T_initial and T_recent
+ *     eligible[b][l] = (ir_mass[b][l] >= gamma): a layer whose mass stays below the threshold gamma
+ *                      is not an I-R layer and is set aside (its byte is 0)
+ * eligible can be handed to krul_select_pairs as is.
+ *
+ *   gamma       threshold, finite and >= 0
+ *   ir_mass     [B][L] float   device, may be NULL
+ *   eligible    [B][L] uint8   device, may be NULL (not both NULL)
+ *   workspace   at least krul_pair_similarity_ir_workspace() bytes (more than the plain call needs)
+ * Everything else, and the error behaviour, is as for krul_pair_similarity.
+ */
+size_t krul_pair_similarity_ir_workspace(const krul_shape_t *shape);
+int krul_pair_similarity_ir(const krul_shape_t *shape, const void *q, const void *k, float gamma,
+                            float *pair_score, float *head_score, float *pair_dist,
+                            float *ir_mass, uint8_t *eligible,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * krul_pair_similarity with two caller-created HIP events (hipEvent_t passed as void*,
  * either may be NULL) recorded on the stream immediately before and after the
  * similarity kernel -- the kernel that forms the logits and the softmax sums and

@@ -57,6 +57,11 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp, sz, vp]
         L.krul_pair_similarity_timed.restype = ctypes.c_int
         L.krul_pair_similarity_timed.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
+        L.krul_pair_similarity_ir_workspace.restype = sz
+        L.krul_pair_similarity_ir_workspace.argtypes = [ctypes.POINTER(KrulShape)]
+        L.krul_pair_similarity_ir.restype = ctypes.c_int
+        L.krul_pair_similarity_ir.argtypes = [ctypes.POINTER(KrulShape), vp, vp, ctypes.c_float, vp, vp, vp, vp, vp,
+                                              vp, sz, vp]
         L.krul_select_pairs.restype = ctypes.c_int
         L.krul_select_pairs.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
         L.krul_calibration_copy.restype = ctypes.c_int
@@ -92,6 +97,10 @@ def make_shape(q: torch.Tensor, k: torch.Tensor, scale: float = 0.0, flags: int 
 
 def workspace_bytes(shape: KrulShape) -> int:
     return int(lib().krul_pair_similarity_workspace(ctypes.byref(shape)))
+
+
+def workspace_bytes_ir(shape: KrulShape) -> int:
+    return int(lib().krul_pair_similarity_ir_workspace(ctypes.byref(shape)))
 
 
 def _stream_ptr() -> int:
@@ -144,6 +153,38 @@ def pair_similarity(q: torch.Tensor, k: torch.Tensor, *, scale: float = 0.0, fla
     if rc != KRUL_OK:
         raise KrulError(rc)
     return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace}
+
+
+def pair_similarity_ir(q: torch.Tensor, k: torch.Tensor, gamma: float, *, scale: float = 0.0, flags: int = 0,
+                       want_head_score: bool = True, want_pair_dist: bool = True,
+                       workspace: torch.Tensor | None = None) -> dict:
+    """krul_pair_similarity_ir on the current stream: the outputs of pair_similarity plus
+    ir_mass [B,L] float32 and eligible [B,L] uint8 (the Initial-Recent layer test)."""
+    if not (q.is_cuda and k.is_cuda):
+        raise ValueError("q and k must be GPU tensors (this library has no CPU path)")
+    if not (q.is_contiguous() and k.is_contiguous()):
+        raise ValueError("q and k must be contiguous")
+    shp = make_shape(q, k, scale, flags)
+    need = workspace_bytes_ir(shp)
+    if need == 0:
+        rc = lib().krul_pair_similarity_ir(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), float(gamma), None, None,
+                                           None, None, None, None, 0, None)
+        raise KrulError(rc if rc != 0 else KRUL_EINVAL)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    B, L, Hq = shp.batch, shp.n_layers, shp.n_q_heads
+    ps = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
+    hs = torch.empty((B, L - 1, Hq), dtype=torch.float32, device=q.device) if want_head_score else None
+    pd = torch.empty((B, L - 1), dtype=torch.float32, device=q.device) if want_pair_dist else None
+    mass = torch.empty((B, L), dtype=torch.float32, device=q.device)
+    el = torch.empty((B, L), dtype=torch.uint8, device=q.device)
+    rc = lib().krul_pair_similarity_ir(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), float(gamma), _dev_ptr(ps),
+                                       _dev_ptr(hs), _dev_ptr(pd), _dev_ptr(mass), _dev_ptr(el),
+                                       _dev_ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "ir_mass": mass, "eligible": el,
+            "workspace": workspace}
 
 
 def select_pairs(pair_score: torch.Tensor, n_select: int, eligible: torch.Tensor | None = None,

@@ -29,7 +29,7 @@ int check_shape(const krul_shape_t *s)
 
 }  // namespace
 
-int make_plan(const krul_shape_t *s, Plan *pl)
+int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
 {
     const int rc = check_shape(s);
     if (rc != KRUL_OK) return rc;
@@ -95,6 +95,13 @@ int make_plan(const krul_shape_t *s, Plan *pl)
     pl->head_cos_off = pl->spill_off + pl->spill_bytes;
     pl->head_dist_off = pl->head_cos_off + head_bytes;
     pl->total_bytes = pl->head_dist_off + head_bytes;
+    pl->state_ir_off = pl->spill_ir_off = pl->head_ir_off = 0;
+    if (want_ir) {
+        pl->state_ir_off = pl->total_bytes;
+        pl->spill_ir_off = pl->state_ir_off + round_up((size_t)records * sizeof(float), kAlign);
+        pl->head_ir_off = pl->spill_ir_off + round_up((size_t)spill_records * sizeof(float), kAlign);
+        pl->total_bytes = pl->head_ir_off + round_up((size_t)(B * L * Hq) * sizeof(float), kAlign);
+    }
     return KRUL_OK;
 }
 
@@ -108,6 +115,73 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__re
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+}  // namespace
+
+namespace {
+// The one implementation behind the similarity entry points.  ir: also run the Initial-Recent layer
+// test (gamma, ir_mass, eligible as for krul_pair_similarity_ir).
+int run_similarity(const krul_shape_t *shape, const void *q, const void *k, float *pair_score,
+                   float *head_score, float *pair_dist, bool ir, float gamma, float *ir_mass,
+                   uint8_t *eligible, void *workspace, size_t workspace_bytes, void *stream,
+                   void *event_begin, void *event_end)
+{
+    Plan pl;
+    const int rc = make_plan(shape, &pl, ir);
+    if (rc != KRUL_OK) return rc;
+    if (!q || !k || !pair_score) return KRUL_EINVAL;
+    if (((uintptr_t)q | (uintptr_t)k) & 15) return KRUL_EINVAL;
+    if (((uintptr_t)pair_score | (uintptr_t)head_score | (uintptr_t)pair_dist | (uintptr_t)ir_mass) & 3)
+        return KRUL_EINVAL;
+    if (ir && (!(gamma >= 0.f) || !isfinite(gamma) || (!ir_mass && !eligible))) return KRUL_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & (kAlign - 1)) || workspace_bytes < pl.total_bytes)
+        return KRUL_EWORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    SimParams p;
+    p.q = q;
+    p.k = k;
+    p.state = reinterpret_cast<float4 *>(ws);
+    p.spill = reinterpret_cast<float4 *>(ws + pl.spill_off);
+    p.B = shape->batch;
+    p.L = shape->n_layers;
+    p.Hq = shape->n_q_heads;
+    p.Hkv = shape->n_kv_heads;
+    p.g = p.Hq / p.Hkv;
+    p.d = shape->head_dim;
+    p.S = shape->n_hist;
+    p.Tq = shape->n_query;
+    p.keys_per_split = pl.keys_per_split;
+    p.c = pl.c;
+    p.want_dist = pair_dist != nullptr || ir;   // the test needs Z as well
+    p.want_ir = ir;
+    // T_initial = T[:10% s], T_recent = T[90% s:] (Sec. 4.2): keys [0, floor(0.1 S)) and [floor(0.9 S), S)
+    p.ir_init_end = (int)floor(0.1 * (double)p.S);
+    p.ir_recent_begin = (int)floor(0.9 * (double)p.S);
+    p.state_ir = reinterpret_cast<float *>(ws + pl.state_ir_off);
+    p.spill_ir = reinterpret_cast<float *>(ws + pl.spill_ir_off);
+    p.lay = pl.lay;
+
+    if (event_begin && hipEventRecord(static_cast<hipEvent_t>(event_begin), st) != hipSuccess)
+        return KRUL_ELAUNCH;
+    hipError_t e = pl.lay.variant == kGeneric
+                       ? launch_sim_generic(p, shape->dtype, pl.n_workgroups, st)
+                       : launch_sim_mfma(p, pl.n_workgroups, st);
+    if (e != hipSuccess) return KRUL_ELAUNCH;
+    if (event_end && hipEventRecord(static_cast<hipEvent_t>(event_end), st) != hipSuccess)
+        return KRUL_ELAUNCH;
+    float *head_cos = head_score ? head_score : reinterpret_cast<float *>(ws + pl.head_cos_off);
+    float *head_dist = reinterpret_cast<float *>(ws + pl.head_dist_off);
+    e = launch_finalize(pl.lay, p.state, p.B, p.L, p.Hq, p.Hkv, p.Tq, head_cos, head_dist,
+                        pair_score, pair_dist, st);
+    if (e != hipSuccess) return KRUL_ELAUNCH;
+    if (ir) {
+        e = launch_finalize_ir(pl.lay, p.state, p.state_ir, p.B, p.L, p.Hq, p.Hkv, p.Tq, gamma,
+                               reinterpret_cast<float *>(ws + pl.head_ir_off), ir_mass, eligible, st);
+        if (e != hipSuccess) return KRUL_ELAUNCH;
+    }
+    return KRUL_OK;
 }
 }  // namespace
 
@@ -142,48 +216,24 @@ int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const v
                                void *workspace, size_t workspace_bytes, void *stream,
                                void *event_begin, void *event_end)
 {
+    return run_similarity(shape, q, k, pair_score, head_score, pair_dist, false, 0.f, nullptr, nullptr,
+                          workspace, workspace_bytes, stream, event_begin, event_end);
+}
+
+size_t krul_pair_similarity_ir_workspace(const krul_shape_t *shape)
+{
     Plan pl;
-    const int rc = make_plan(shape, &pl);
-    if (rc != KRUL_OK) return rc;
-    if (!q || !k || !pair_score) return KRUL_EINVAL;
-    if (((uintptr_t)q | (uintptr_t)k) & 15) return KRUL_EINVAL;
-    if (((uintptr_t)pair_score | (uintptr_t)head_score | (uintptr_t)pair_dist) & 3) return KRUL_EINVAL;
-    if (!workspace || ((uintptr_t)workspace & (kAlign - 1)) || workspace_bytes < pl.total_bytes)
-        return KRUL_EWORKSPACE;
+    if (make_plan(shape, &pl, true) != KRUL_OK) return 0;
+    return pl.total_bytes;
+}
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    unsigned char *ws = static_cast<unsigned char *>(workspace);
-    SimParams p;
-    p.q = q;
-    p.k = k;
-    p.state = reinterpret_cast<float4 *>(ws);
-    p.spill = reinterpret_cast<float4 *>(ws + pl.spill_off);
-    p.B = shape->batch;
-    p.L = shape->n_layers;
-    p.Hq = shape->n_q_heads;
-    p.Hkv = shape->n_kv_heads;
-    p.g = p.Hq / p.Hkv;
-    p.d = shape->head_dim;
-    p.S = shape->n_hist;
-    p.Tq = shape->n_query;
-    p.keys_per_split = pl.keys_per_split;
-    p.c = pl.c;
-    p.want_dist = pair_dist != nullptr;
-    p.lay = pl.lay;
-
-    if (event_begin && hipEventRecord(static_cast<hipEvent_t>(event_begin), st) != hipSuccess)
-        return KRUL_ELAUNCH;
-    hipError_t e = pl.lay.variant == kGeneric
-                       ? launch_sim_generic(p, shape->dtype, pl.n_workgroups, st)
-                       : launch_sim_mfma(p, pl.n_workgroups, st);
-    if (e != hipSuccess) return KRUL_ELAUNCH;
-    if (event_end && hipEventRecord(static_cast<hipEvent_t>(event_end), st) != hipSuccess)
-        return KRUL_ELAUNCH;
-    float *head_cos = head_score ? head_score : reinterpret_cast<float *>(ws + pl.head_cos_off);
-    float *head_dist = reinterpret_cast<float *>(ws + pl.head_dist_off);
-    e = launch_finalize(pl.lay, p.state, p.B, p.L, p.Hq, p.Hkv, p.Tq, head_cos, head_dist,
-                        pair_score, pair_dist, st);
-    return e == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
+int krul_pair_similarity_ir(const krul_shape_t *shape, const void *q, const void *k, float gamma,
+                            float *pair_score, float *head_score, float *pair_dist,
+                            float *ir_mass, uint8_t *eligible,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_similarity(shape, q, k, pair_score, head_score, pair_dist, true, gamma, ir_mass, eligible,
+                          workspace, workspace_bytes, stream, nullptr, nullptr);
 }
 
 int krul_select_pairs(const float *pair_score, const uint8_t *eligible,

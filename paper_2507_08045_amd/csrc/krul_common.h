@@ -56,11 +56,13 @@ struct Plan {
     size_t state_bytes;  // merged partial records (float4), read by the finalize kernel
     size_t spill_bytes;  // per-lane running records of multi-tile splits (MFMA variants)
     size_t spill_off, head_cos_off, head_dist_off, total_bytes;
+    // Initial-Recent layer test only: one float per record beside state / spill, head means
+    size_t state_ir_off, spill_ir_off, head_ir_off;
 };
 
 // Host: choose kernel and decomposition for a validated shape.  Returns a
 // krul_status_t.
-int make_plan(const krul_shape_t *s, Plan *plan);
+int make_plan(const krul_shape_t *s, Plan *plan, bool want_ir = false);
 
 struct SimParams {
     const void *q;
@@ -71,6 +73,11 @@ struct SimParams {
     int keys_per_split;
     float c;
     int want_dist;   // the distance is asked for: Z = sum e must be accumulated too
+    // Initial-Recent layer test (Sec. 4.2, Alg. 1 first loop): Zir = sum of e over the keys
+    // [0, ir_init_end) and [ir_recent_begin, S), one float per record, laid out like state / spill
+    int want_ir;
+    int ir_init_end, ir_recent_begin;
+    float *state_ir, *spill_ir;
     StateLayout lay;
 };
 
@@ -80,6 +87,11 @@ hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
 hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, int L, int Hq, int Hkv,
                            int Tq, float *head_cos, float *head_dist, float *pair_cos,
                            float *pair_dist, hipStream_t st);   // pair_dist may be null
+// Initial-Recent mass per layer from the (m, Z) records and the Zir values: mean over rows and heads of
+// Zir / Z; eligible = (mass >= gamma).  head_ir is scratch [B][L][Hq]; ir_mass or eligible may be null.
+hipError_t launch_finalize_ir(const StateLayout &lay, const float4 *state, const float *state_ir, int B, int L,
+                              int Hq, int Hkv, int Tq, float gamma, float *head_ir, float *ir_mass,
+                              uint8_t *eligible, hipStream_t st);
 hipError_t launch_select(const float *pair_score, const uint8_t *eligible, int batch, int n_layers,
                          int n_select, int32_t *out_pairs, int32_t *out_count, hipStream_t st);
 

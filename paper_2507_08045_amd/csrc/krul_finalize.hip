@@ -117,7 +117,84 @@ __global__ void finalize_pairs_kernel(int n_pairs_total, int Hq, const float *__
     if (pair_dist) pair_dist[i] = ds / (float)Hq;
 }
 
+// Initial-Recent layer test (Sec. 4.2; Alg. 1 first loop): per (conversation, layer, head) the
+// mean over query rows of Zir / Z -- the attention mass on T_initial and T_recent -- from the
+// partial records of each row, merged onto a common exponent like the similarity sums.
+__global__ __launch_bounds__(kThreads) void ir_heads_kernel(
+    StateLayout lay, const float4 *__restrict__ state, const float *__restrict__ state_ir, int L, int Hq,
+    int Hkv, int Tq, int G, float *__restrict__ head_ir)
+{
+    __shared__ float red[kThreads / 64];
+    const int h = blockIdx.x % Hq;
+    const int l = (blockIdx.x / Hq) % L;
+    const int b = blockIdx.x / (Hq * L);
+    const int g_heads = Hq / Hkv;
+    const int u = b * Hkv + h / g_heads;
+    const int P = lay.partials;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int RW = 64 / G;                       // rows per wave, G lanes per row
+    const int rr = lane % RW, g = lane / RW;
+
+    float mass_acc = 0.f;
+    for (int t0 = 0; t0 < Tq; t0 += (kThreads / 64) * RW) {
+        const int t = t0 + wave * RW + rr;
+        float M = kMInit, Z = 0.f, I = 0.f;
+        if (t < Tq) {
+            const int r = (h % g_heads) * Tq + t;
+            for (int pi = g; pi < P; pi += G) {
+                const size_t idx = state_index(lay, u, r, pi, l);
+                const float4 a = state[idx];
+                const float zi = state_ir[idx];
+                const float Mn = fmaxf(M, a.x);
+                const float f0 = exp2f(M - Mn), f1 = exp2f(a.x - Mn);
+                Z = Z * f0 + a.y * f1;
+                I = I * f0 + zi * f1;
+                M = Mn;
+            }
+        }
+        for (int off = 32; off >= RW; off >>= 1) {
+            const float m2 = __shfl_xor(M, off, 64), z2 = __shfl_xor(Z, off, 64), i2 = __shfl_xor(I, off, 64);
+            const float Mn = fmaxf(M, m2);
+            const float f0 = exp2f(M - Mn), f1 = exp2f(m2 - Mn);
+            Z = Z * f0 + z2 * f1;
+            I = I * f0 + i2 * f1;
+            M = Mn;
+        }
+        if (t < Tq && g == 0) mass_acc += I / Z;
+    }
+    const float ms = block_sum(mass_acc, red);
+    if (threadIdx.x == 0) head_ir[blockIdx.x] = ms / (float)Tq;
+}
+
+// one thread per (conversation, layer): the average over heads, and the test against gamma
+__global__ void ir_layers_kernel(int n_layers_total, int Hq, float gamma, const float *__restrict__ head_ir,
+                                 float *__restrict__ ir_mass, uint8_t *__restrict__ eligible)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_layers_total) return;
+    float m = 0.f;
+    for (int h = 0; h < Hq; ++h) m += head_ir[(size_t)i * Hq + h];
+    m /= (float)Hq;
+    if (ir_mass) ir_mass[i] = m;
+    if (eligible) eligible[i] = m >= gamma ? 1 : 0;   // below gamma: not an Initial-Recent layer, set aside
+}
+
 }  // namespace
+
+hipError_t launch_finalize_ir(const StateLayout &lay, const float4 *state, const float *state_ir, int B, int L,
+                              int Hq, int Hkv, int Tq, float gamma, float *head_ir, float *ir_mass,
+                              uint8_t *eligible, hipStream_t st)
+{
+    int G = 1;
+    while (G < 64 && G * Tq < kThreads && G < lay.partials) G <<= 1;
+    hipLaunchKernelGGL(ir_heads_kernel, dim3(B * L * Hq), dim3(kThreads), 0, st, lay, state, state_ir, L, Hq,
+                       Hkv, Tq, G, head_ir);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(ir_layers_kernel, dim3((B * L + 127) / 128), dim3(128), 0, st, B * L, Hq, gamma, head_ir,
+                       ir_mass, eligible);
+    return hipGetLastError();
+}
 
 hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, int L, int Hq, int Hkv,
                            int Tq, float *head_cos, float *head_dist, float *pair_cos,

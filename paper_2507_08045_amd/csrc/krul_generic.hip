@@ -76,6 +76,7 @@ __global__ __launch_bounds__(64) void sim_generic_kernel(SimParams p)
     extern __shared__ float smem[];
     float4 *st = reinterpret_cast<float4 *>(smem);   // [L] running (m, Z, N2, C)
     float *qs = smem + 4 * p.L;                      // [d] current query row
+    float *st_ir = qs + p.d;                         // [L] running Zir (Initial-Recent layer test)
 
     const int lane = threadIdx.x;
     const int sp = blockIdx.x % p.lay.n_split;
@@ -90,7 +91,10 @@ __global__ __launch_bounds__(64) void sim_generic_kernel(SimParams p)
     const int key_begin = sp * p.keys_per_split;
     const int key_end = min(p.S, key_begin + p.keys_per_split);
 
-    for (int l = lane; l < p.L; l += 64) st[l] = make_float4(kMInit, 0.f, 0.f, 0.f);
+    for (int l = lane; l < p.L; l += 64) {
+        st[l] = make_float4(kMInit, 0.f, 0.f, 0.f);
+        st_ir[l] = 0.f;
+    }
     __syncthreads();
 
     const T *Q = static_cast<const T *>(p.q);
@@ -99,6 +103,7 @@ __global__ __launch_bounds__(64) void sim_generic_kernel(SimParams p)
     for (int key0 = key_begin; key0 < key_end; key0 += 64) {
         const int key = key0 + lane;
         const bool valid = key < key_end;
+        const bool in_ir = valid && (key < p.ir_init_end || key >= p.ir_recent_begin);   // T_initial or T_recent
         float e_prev = 0.f, f_prev = 1.f;
         for (int l = 0; l < p.L; ++l) {
             const size_t qoff = ((((size_t)b * p.L + l) * p.Hq + h) * p.Tq + t) * p.d;
@@ -117,22 +122,29 @@ __global__ __launch_bounds__(64) void sim_generic_kernel(SimParams p)
             const float sz = wave_sum(e);
             const float sn = wave_sum(e * e);
             const float sc = wave_sum(e * e_prev);
+            float si = 0.f;
+            if (p.want_ir) si = wave_sum(in_ir ? e : 0.f);
             __syncthreads();
-            if (lane == 0)
+            if (lane == 0) {
                 st[l] = make_float4(m_new, cur.y * f + sz, cur.z * f * f + sn, cur.w * f * f_prev + sc);
+                st_ir[l] = st_ir[l] * f + si;
+            }
             e_prev = e;
             f_prev = f;
         }
     }
     __syncthreads();
-    for (int l = lane; l < p.L; l += 64) p.state[state_index(p.lay, u, r, sp, l)] = st[l];
+    for (int l = lane; l < p.L; l += 64) {
+        p.state[state_index(p.lay, u, r, sp, l)] = st[l];
+        if (p.want_ir) p.state_ir[state_index(p.lay, u, r, sp, l)] = st_ir[l];
+    }
 }
 
 }  // namespace
 
 hipError_t launch_sim_generic(const SimParams &p, int dtype, int n_workgroups, hipStream_t st)
 {
-    const size_t smem = sizeof(float) * (4 * (size_t)p.L + p.d);
+    const size_t smem = sizeof(float) * (5 * (size_t)p.L + p.d);
     if (dtype == KRUL_F32)
         hipLaunchKernelGGL(sim_generic_kernel<float>, dim3(n_workgroups), dim3(64), smem, st, p);
     else

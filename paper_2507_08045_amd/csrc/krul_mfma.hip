@@ -90,10 +90,13 @@ __device__ inline int swz(int row)
     return D == 128 ? (row & 15) : ((row >> 1) & 7);
 }
 
-template <class C, bool WZ>   // WZ: also accumulate Z = sum e (needed for the distance only)
+// MODE 0: cosine only; 1: also Z = sum e (needed for the distance); 2: also Zir = sum of e over the
+// initial and recent keys (the Initial-Recent layer test of Sec. 4.2), which needs Z too
+template <class C, int MODE>
 __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 {
     constexpr int D = C::D, WK = C::WK, KBW = C::KBW, NC = C::NC, KS = C::KS;
+    constexpr bool WZ = MODE >= 1, IR = MODE == 2;
     constexpr int NLD = C::NLD, PPR = C::PPR, NBLK = C::NBLK, RPI = C::RPI, PF = C::PF;
     // (the larger alignment puts the ring first in the workgroup's LDS, within reach of the
     // 16-bit offset field of the operand reads)
@@ -103,6 +106,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     __shared__ __attribute__((aligned(16384))) unsigned char ring3[NC > 2 ? C::SLOT_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char qlds[C::WR * C::QBYTES];
     __shared__ float4 part[C::NW][64];   // every lane's record of the last step (m, Z, N2, C)
+    __shared__ float part_ir[IR ? C::NW : 1][64];   // ... and its Zir
     auto slot_ptr = [&](int i) __attribute__((always_inline)) -> unsigned char * {
         switch (i) {   // i is a constant at every call site once the loops are unrolled
         case 0: return ring0;
@@ -268,10 +272,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         float M = pp[0].x;
 #pragma unroll
         for (int pi = 1; pi < 2 * WK; ++pi) M = fmaxf(M, pp[pi].x);
-        float zs = 0.f, ns = 0.f, cc = 0.f;
+        float zs = 0.f, ns = 0.f, cc = 0.f, zir = 0.f;
 #pragma unroll
         for (int pi = 0; pi < 2 * WK; ++pi) {
             const float f = __builtin_amdgcn_exp2f(pp[pi].x - M);
+            if (IR) zir = fmaf(part_ir[wr * WK + (pi >> 1)][(pi & 1) * 32 + l32], f, zir);
             zs = fmaf(pp[pi].y, f, zs);
             ns = fmaf(pp[pi].z, f * f, ns);
             cc = fmaf(pp[pi].w, f * gprev[pi], cc);
@@ -279,9 +284,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         }
         // lanes l and l+32 hold, and store, the same record
         p.state[((size_t)wg * L + mg_l) * C::R_WG + wr * 32 + l32] = make_float4(M, zs, ns, cc);
+        if (IR) p.state_ir[((size_t)wg * L + mg_l) * C::R_WG + wr * 32 + l32] = zir;
     };
     // running record of the coming step (its previous tile's), fetched one step ahead
     float4 rec_pre = make_float4(kMInit, 0.f, 0.f, 0.f);
+    float rec_ir_pre = 0.f;
     for (int tile = 0; tile < ntiles; ++tile) {
         const int tile_key0 = key_begin + tile * C::KT;
         const bool ragged = tile_key0 + C::KT > key_end;
@@ -289,6 +296,8 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
         for (int l = 0; l < L; ++l, ++step) {
             const float4 rec = rec_pre;
+            const float rec_ir = rec_ir_pre;
+            float tzir = 0.f;
             // the step after this one: its layer and tile, and where its keys and query rows are
             const bool has_next = step + 1 < nsteps;
             const int ln = l + 1 == L ? 0 : l + 1;
@@ -321,9 +330,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 if (c == 0) {
                     // The next step's running record was written L-1 steps ago (by this lane).
                     rec_pre = make_float4(kMInit, 0.f, 0.f, 0.f);
+                    rec_ir_pre = 0.f;
                     if (tn_ > 0 && has_next) {
                         if (L < 4) __builtin_amdgcn_s_waitcnt(wait_vm(0));   // (then it may still be on its way)
                         rec_pre = spill[spill_index(ln)];
+                        if (IR) rec_ir_pre = p.spill_ir[spill_index(ln)];
                     }
                 }
                 if (c == NC - 1) read_q();   // every wave has the old rows in use no more
@@ -404,6 +415,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                         const float mnew = fmaxf(mcur, tmax * cs);
                         const float f = __builtin_amdgcn_exp2f(mcur - mnew);
                         tz *= f;
+                        tzir *= f;
                         tn *= f * f;
                         mcur = mnew;
                         raised = true;
@@ -421,6 +433,21 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) e[blk][v] = ev[v];
                     tz += bz;
+                    if (IR) {
+                        // keys of this block inside T_initial or T_recent: all, none, or some
+                        const int kb0 = tile_key0 + c * C::CH + (wk * KBW + kb) * 32;
+                        if (kb0 + 32 <= p.ir_init_end || kb0 >= p.ir_recent_begin) {
+                            tzir += bz;
+                        } else if (!(kb0 >= p.ir_init_end && kb0 + 32 <= p.ir_recent_begin)) {
+                            float bir = 0.f;   // element v of this lane is key kb0 + 8*(v/4) + 4*half + v%4
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) {
+                                const int key = kb0 + 8 * (v >> 2) + 4 * half + (v & 3);
+                                if (key < p.ir_init_end || key >= p.ir_recent_begin) bir += ev[v];
+                            }
+                            tzir += bir;
+                        }
+                    }
                     tn += bn;
                     dot[blk] = bd;
                 }
@@ -444,8 +471,10 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
             // ---- fold this tile's sums into the running record of layer l
             float4 out;
+            float out_ir = 0.f;
             {
                 const float F = __builtin_amdgcn_exp2f(rec.x - mcur);
+                if (IR) out_ir = fmaf(rec_ir, F, tzir);
                 out.x = mcur;
                 out.y = fmaf(rec.y, F, tz);
                 out.z = fmaf(rec.z, F * F, tn);
@@ -454,9 +483,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
             }
             if (!last_tile) {
                 spill[spill_index(l)] = out;
+                if (IR) p.spill_ir[spill_index(l)] = out_ir;
             } else {
                 // ---- post this lane's record; the merge follows during the next step
                 part[wave][lane] = out;
+                if (IR) part_ir[wave][lane] = out_ir;
                 mg_l = l;
                 mg_on = true;
             }
@@ -473,10 +504,12 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 template <class C>
 hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
 {
-    if (p.want_dist)
-        hipLaunchKernelGGL((sim_mfma_kernel<C, true>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
+    if (p.want_ir)
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 2>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
+    else if (p.want_dist)
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 1>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
     else
-        hipLaunchKernelGGL((sim_mfma_kernel<C, false>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 0>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
     return hipGetLastError();
 }
 
