@@ -31,7 +31,8 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(kr):
     names = declared_functions()
     assert {"krul_pair_similarity", "krul_select_pairs", "krul_pair_similarity_workspace",
-            "krul_n_select_from_ratio", "krul_strerror", "krul_pair_similarity_timed"} <= set(names)
+            "krul_n_select_from_ratio", "krul_strerror", "krul_pair_similarity_timed",
+            "krul_pair_similarity_ir", "krul_pair_similarity_ir_workspace"} <= set(names)
     lib = kr.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in krul.h but not exported"
@@ -97,6 +98,27 @@ def test_pair_similarity_rejects_bad_arguments_before_any_gpu_work(kr):
     assert call_sim(kr, ok, ws=0x10010) == kr.KRUL_EWORKSPACE      # 256-byte alignment
     assert call_sim(kr, ok, ws_bytes=need - 1) == kr.KRUL_EWORKSPACE
     assert kr.lib().krul_pair_similarity(None, None, None, None, None, None, None, 0, None) == kr.KRUL_EINVAL
+
+
+def test_ir_entry_point_rejects_bad_arguments_before_any_gpu_work(kr):
+    vp = ctypes.c_void_p
+    ok = shape(kr)
+    need = kr.workspace_bytes_ir(ok)
+    assert need > kr.workspace_bytes(ok) and need % 256 == 0
+    assert kr.workspace_bytes_ir(shape(kr, L=1)) == 0
+
+    def call(shp, gamma=0.3, ps=0x3000, mass=0x4000, el=0x5000, ws=0x10000, ws_bytes=1 << 40):
+        return kr.lib().krul_pair_similarity_ir(ctypes.byref(shp), vp(0x1000), vp(0x2000), ctypes.c_float(gamma),
+                                                vp(ps), None, None, vp(mass), vp(el), vp(ws),
+                                                ctypes.c_size_t(ws_bytes), None)
+    assert call(shape(kr, Hq=3)) == kr.KRUL_EINVAL
+    assert call(ok, gamma=-0.1) == kr.KRUL_EINVAL
+    assert call(ok, gamma=float("nan")) == kr.KRUL_EINVAL
+    assert call(ok, mass=None, el=None) == kr.KRUL_EINVAL          # nothing to write the test's result to
+    assert call(ok, ps=None) == kr.KRUL_EINVAL
+    assert call(ok, mass=0x4002) == kr.KRUL_EINVAL                 # float alignment
+    assert call(ok, ws_bytes=need - 1) == kr.KRUL_EWORKSPACE
+    assert call(ok, ws_bytes=kr.workspace_bytes(ok)) == kr.KRUL_EWORKSPACE   # the plain call's size is too small
 
 
 def test_select_pairs_rejects_bad_arguments(kr):
