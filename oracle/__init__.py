@@ -30,7 +30,7 @@ class _Shape(ctypes.Structure):
         ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
         ("head_dim", ctypes.c_int32), ("n_hist", ctypes.c_int32),
         ("n_query", ctypes.c_int32), ("dtype", ctypes.c_int32),
-        ("scale", ctypes.c_double),
+        ("scale", ctypes.c_double), ("causal", ctypes.c_int32),
     ]
 
 
@@ -59,7 +59,7 @@ def num_threads() -> int:
     return int(_load().krul_oracle_num_threads())
 
 
-def _prep(q: np.ndarray, k: np.ndarray, scale):
+def _prep(q: np.ndarray, k: np.ndarray, scale, causal=False):
     if q.ndim != 5 or k.ndim != 5:
         raise ValueError("q must be [B,L,Hq,Tq,d] and k [B,L,Hkv,S,d]")
     if q.dtype != k.dtype:
@@ -76,7 +76,7 @@ def _prep(q: np.ndarray, k: np.ndarray, scale):
         raise ValueError("q and k disagree on batch, layers or head_dim")
     q = np.ascontiguousarray(q)
     k = np.ascontiguousarray(k)
-    shp = _Shape(B, L, Hq, Hkv, d, S, Tq, dt, float(scale) if scale else 0.0)
+    shp = _Shape(B, L, Hq, Hkv, d, S, Tq, dt, float(scale) if scale else 0.0, 1 if causal else 0)
     return q, k, shp
 
 
@@ -84,10 +84,11 @@ def _ptr(a: np.ndarray):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
-def pair_similarity(q: np.ndarray, k: np.ndarray, scale=None) -> dict:
+def pair_similarity(q: np.ndarray, k: np.ndarray, scale=None, causal=False) -> dict:
     """All scores: dict with pair_score [B,L-1], head_score [B,L-1,Hq] (cosine) and
-    pair_dist, head_dist (Euclidean), all float64."""
-    q, k, shp = _prep(q, k, scale)
+    pair_dist, head_dist (Euclidean), all float64.  causal: the Tq rows are the last Tq tokens of
+    the S-token sequence and row t sees keys j <= S - Tq + t."""
+    q, k, shp = _prep(q, k, scale, causal)
     B, NP, H = shp.batch, shp.n_layers - 1, shp.n_q_heads
     out = {
         "pair_score": np.empty((B, NP)), "head_score": np.empty((B, NP, H)),
@@ -101,9 +102,9 @@ def pair_similarity(q: np.ndarray, k: np.ndarray, scale=None) -> dict:
     return out
 
 
-def unit_scores(q: np.ndarray, k: np.ndarray, units, scale=None):
+def unit_scores(q: np.ndarray, k: np.ndarray, units, scale=None, causal=False):
     """Scores of chosen (b, l, h) units only: returns (head_cos[n], head_dist[n])."""
-    q, k, shp = _prep(q, k, scale)
+    q, k, shp = _prep(q, k, scale, causal)
     units = np.ascontiguousarray(np.asarray(units, dtype=np.int32).reshape(-1, 3))
     n = units.shape[0]
     hc, hd = np.empty(n), np.empty(n)

@@ -25,7 +25,8 @@
  *
  * Readings taken where the paper leaves a choice (adjacent pairs only, row-wise
  * similarity then mean, grouped-query head mapping h -> h / (Hq/Hkv), no mask
- * between query tokens, stable tie-break on the lower layer index) are listed in
+ * between query tokens unless the causal reading is asked for, stable tie-break on
+ * the lower layer index) are listed in
  * the design notes of the repository; each is marked below where it is applied.
  *
  * Every function here is pinned by tests that do not re-use this code: closed
@@ -48,6 +49,10 @@ typedef struct {
     int32_t batch, n_layers, n_q_heads, n_kv_heads, head_dim, n_hist, n_query;
     int32_t dtype;   /* ORACLE_F32 or ORACLE_BF16 (raw 16-bit patterns) */
     double scale;    /* <= 0 means 1/sqrt(head_dim)  (Sec. 2.1) */
+    int32_t causal;  /* 0: every query row sees all n_hist keys.  1: the n_query rows are the last
+                        n_query tokens of the n_hist-token sequence and row t sees the keys up to
+                        and including its own position, j <= n_hist - n_query + t (decode, Sec. 5:
+                        a generated token attends to all previous tokens; chunked prefill) */
 } oracle_shape_t;
 
 /* Exact widening of one stored element to double. */
@@ -69,8 +74,9 @@ static double eff_scale(const oracle_shape_t *s)
 /*
  * Attention weights of layer l, query head h of conversation b: P[t*S + j],
  * t < Tq, j < S.  Sec. 2.1: softmax over the keys of (q . k) / sqrt(d_K).
- * Query head h reads kv head h / (Hq/Hkv) (grouped-query reading).  No mask:
- * every query row sees all S history keys.
+ * Query head h reads kv head h / (Hq/Hkv) (grouped-query reading).  Without the
+ * causal reading every query row sees all S keys; with it row t sees keys
+ * j <= S - Tq + t and the weights of the later keys are exactly 0.
  */
 static void attention_weights(const oracle_shape_t *s, const void *q, const void *k,
                               int b, int l, int h, double *P)
@@ -86,8 +92,9 @@ static void attention_weights(const oracle_shape_t *s, const void *q, const void
         double *row = P + (size_t)t * S;
         for (int i = 0; i < d; ++i)
             qrow[i] = elem(q, s->dtype, qbase + (size_t)t * d + i);
+        const int vis = s->causal ? S - Tq + t + 1 : S;   /* keys 0 .. vis-1 are visible */
         double mx = -INFINITY;
-        for (int j = 0; j < S; ++j) {
+        for (int j = 0; j < vis; ++j) {
             double acc = 0.0;
             for (int i = 0; i < d; ++i)
                 acc += qrow[i] * elem(k, s->dtype, kbase + (size_t)j * d + i);
@@ -95,12 +102,14 @@ static void attention_weights(const oracle_shape_t *s, const void *q, const void
             if (row[j] > mx) mx = row[j];
         }
         double z = 0.0;
-        for (int j = 0; j < S; ++j) {
+        for (int j = 0; j < vis; ++j) {
             row[j] = exp(row[j] - mx);
             z += row[j];
         }
-        for (int j = 0; j < S; ++j)
+        for (int j = 0; j < vis; ++j)
             row[j] /= z;
+        for (int j = vis; j < S; ++j)
+            row[j] = 0.0;
     }
     free(qrow);
 }
@@ -142,7 +151,8 @@ static int shape_ok(const oracle_shape_t *s)
 {
     return s && s->batch > 0 && s->n_layers >= 2 && s->n_q_heads > 0 && s->n_kv_heads > 0 &&
            s->n_q_heads % s->n_kv_heads == 0 && s->head_dim > 0 && s->n_hist > 0 &&
-           s->n_query > 0 && (s->dtype == ORACLE_F32 || s->dtype == ORACLE_BF16);
+           s->n_query > 0 && (s->dtype == ORACLE_F32 || s->dtype == ORACLE_BF16) &&
+           (s->causal == 0 || (s->causal == 1 && s->n_hist >= s->n_query));
 }
 
 /*
@@ -276,7 +286,7 @@ int krul_oracle_select_pairs(const double *pair_score, const uint8_t *eligible,
 int krul_oracle_ir_mass(const oracle_shape_t *s, const void *q, const void *k,
                         double gamma, double *mass, uint8_t *eligible)
 {
-    if (!shape_ok(s) || !q || !k)
+    if (!shape_ok(s) || !q || !k || s->causal)   /* the test is stated for whole-sequence attention */
         return -1;
     const int B = s->batch, L = s->n_layers, H = s->n_q_heads, S = s->n_hist, Tq = s->n_query;
     const int n_init = (int)floor(0.1 * (double)S);
