@@ -38,6 +38,11 @@ typedef enum { KRUL_F32 = 0, KRUL_BF16 = 1 } krul_dtype_t;
 
 /* flags of krul_shape_t */
 enum {
+    KRUL_FLAG_CAUSAL = 1 << 0,         /* the n_query rows are the LAST n_query tokens of the n_hist-token
+                                          sequence held by k, and row t attends to the keys up to and
+                                          including its own position, j <= n_hist - n_query + t (a decode
+                                          step, n_query = 1, or a chunk of a prefill; Sec. 5).  Needs
+                                          n_hist >= n_query.  Without it every row sees all n_hist keys. */
     KRUL_FLAG_GENERIC_KERNEL = 1 << 8, /* testing aid: use the portable VALU kernel even where the
                                           MFMA kernel applies (results agree to rounding) */
     KRUL_FLAG_SINGLE_SPLIT = 1 << 9    /* do not split a row's keys over several workgroups
@@ -107,6 +112,7 @@ int krul_pair_similarity(const krul_shape_t *shape, const void *q, const void *k
  *                      is not an I-R layer and is set aside (its byte is 0)
  * eligible can be handed to krul_select_pairs as is.
  *
+ *   (not available together with KRUL_FLAG_CAUSAL: the test is stated for whole-sequence attention)
  *   gamma       threshold, finite and >= 0
  *   ir_mass     [B][L] float   device, may be NULL
  *   eligible    [B][L] uint8   device, may be NULL (not both NULL)
@@ -118,6 +124,31 @@ int krul_pair_similarity_ir(const krul_shape_t *shape, const void *q, const void
                             float *pair_score, float *head_score, float *pair_dist,
                             float *ir_mass, uint8_t *eligible,
                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Token-wise accumulation over several calls (Sec. 5 and Sec. 7: the similarities of the tokens of
+ * the prefill and of every decode step are added up).  krul_pair_similarity_accumulate adds, for every
+ * (conversation, pair, query head), the SUM over this call's n_query rows of the row cosine to
+ * head_sum, and of the row distance to head_dist_sum; the caller zeroes the sums before the first
+ * call and counts the tokens.  Typical use: one call per prefill chunk or decode step with
+ * KRUL_FLAG_CAUSAL, k holding the sequence so far.  krul_pair_scores_from_sums then turns the sums
+ * into the scores krul_pair_similarity would give: head_score = head_sum / n_tokens,
+ * pair_score = mean over heads (likewise pair_dist).
+ *
+ *   head_sum       [B][L-1][Hq] float  device, required, read and written (+=)
+ *   head_dist_sum  [B][L-1][Hq] float  device, may be NULL
+ *   n_tokens       rows accumulated per head so far (> 0)
+ *   pair_score [B][L-1] required; head_score [B][L-1][Hq], pair_dist [B][L-1] may be NULL
+ *   (pair_dist needs head_dist_sum)
+ * Calls on one stream are ordered; concurrent calls that share sums race.  Errors as for
+ * krul_pair_similarity.
+ */
+int krul_pair_similarity_accumulate(const krul_shape_t *shape, const void *q, const void *k,
+                                    float *head_sum, float *head_dist_sum,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+int krul_pair_scores_from_sums(const float *head_sum, const float *head_dist_sum,
+                               int32_t batch, int32_t n_layers, int32_t n_q_heads, float n_tokens,
+                               float *pair_score, float *head_score, float *pair_dist, void *stream);
 
 /*
  * krul_pair_similarity with two caller-created HIP events (hipEvent_t passed as void*,

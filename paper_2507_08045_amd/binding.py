@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libkrul.so")
 
 KRUL_OK, KRUL_EINVAL, KRUL_EDTYPE, KRUL_EWORKSPACE, KRUL_ELAUNCH, KRUL_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 KRUL_F32, KRUL_BF16 = 0, 1
+KRUL_FLAG_CAUSAL = 1 << 0
 KRUL_FLAG_GENERIC_KERNEL = 1 << 8
 KRUL_FLAG_SINGLE_SPLIT = 1 << 9
 
@@ -62,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_ir.restype = ctypes.c_int
         L.krul_pair_similarity_ir.argtypes = [ctypes.POINTER(KrulShape), vp, vp, ctypes.c_float, vp, vp, vp, vp, vp,
                                               vp, sz, vp]
+        L.krul_pair_similarity_accumulate.restype = ctypes.c_int
+        L.krul_pair_similarity_accumulate.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, sz, vp]
+        L.krul_pair_scores_from_sums.restype = ctypes.c_int
+        L.krul_pair_scores_from_sums.argtypes = [vp, vp, i32, i32, i32, ctypes.c_float, vp, vp, vp, vp]
         L.krul_select_pairs.restype = ctypes.c_int
         L.krul_select_pairs.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
         L.krul_calibration_copy.restype = ctypes.c_int
@@ -185,6 +190,46 @@ def pair_similarity_ir(q: torch.Tensor, k: torch.Tensor, gamma: float, *, scale:
         raise KrulError(rc)
     return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "ir_mass": mass, "eligible": el,
             "workspace": workspace}
+
+
+def pair_similarity_accumulate(q: torch.Tensor, k: torch.Tensor, head_sum: torch.Tensor,
+                               head_dist_sum: torch.Tensor | None = None, *, scale: float = 0.0, flags: int = 0,
+                               workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """krul_pair_similarity_accumulate on the current stream: adds this call's per-row cosines (and
+    distances) to the running sums head_sum (head_dist_sum), both [B,L-1,Hq] float32.  Returns the workspace."""
+    if not (q.is_cuda and k.is_cuda and q.is_contiguous() and k.is_contiguous()):
+        raise ValueError("q and k must be contiguous GPU tensors (this library has no CPU path)")
+    shp = make_shape(q, k, scale, flags)
+    want = (shp.batch, shp.n_layers - 1, shp.n_q_heads)
+    for t in (head_sum, head_dist_sum):
+        if t is not None and (not t.is_cuda or t.dtype != torch.float32 or tuple(t.shape) != want
+                              or not t.is_contiguous()):
+            raise ValueError("the running sums must be contiguous float32 GPU tensors [B, L-1, Hq]")
+    need = workspace_bytes(shp)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = lib().krul_pair_similarity_accumulate(
+        ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), _dev_ptr(head_sum), _dev_ptr(head_dist_sum),
+        _dev_ptr(workspace), workspace.numel() if workspace is not None else 0, ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return workspace
+
+
+def pair_scores_from_sums(head_sum: torch.Tensor, n_tokens: float, head_dist_sum: torch.Tensor | None = None) -> dict:
+    """krul_pair_scores_from_sums: running sums over n_tokens rows -> pair_score, head_score, pair_dist."""
+    if not head_sum.is_cuda or head_sum.dtype != torch.float32 or head_sum.dim() != 3 or not head_sum.is_contiguous():
+        raise ValueError("head_sum must be a contiguous float32 GPU tensor [B, L-1, Hq]")
+    B, NP, Hq = head_sum.shape
+    ps = torch.empty((B, NP), dtype=torch.float32, device=head_sum.device)
+    hs = torch.empty((B, NP, Hq), dtype=torch.float32, device=head_sum.device)
+    pd = torch.empty((B, NP), dtype=torch.float32, device=head_sum.device) if head_dist_sum is not None else None
+    rc = lib().krul_pair_scores_from_sums(_dev_ptr(head_sum), _dev_ptr(head_dist_sum), B, NP + 1, Hq,
+                                          float(n_tokens), _dev_ptr(ps), _dev_ptr(hs), _dev_ptr(pd),
+                                          ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return {"pair_score": ps, "head_score": hs, "pair_dist": pd}
 
 
 def select_pairs(pair_score: torch.Tensor, n_select: int, eligible: torch.Tensor | None = None,

@@ -21,7 +21,8 @@ int check_shape(const krul_shape_t *s)
         return KRUL_EINVAL;
     if (s->n_q_heads % s->n_kv_heads != 0) return KRUL_EINVAL;
     if (!(s->scale >= 0.f) || !isfinite(s->scale)) return KRUL_EINVAL;
-    if (s->flags & ~(KRUL_FLAG_GENERIC_KERNEL | KRUL_FLAG_SINGLE_SPLIT)) return KRUL_EINVAL;
+    if (s->flags & ~(KRUL_FLAG_CAUSAL | KRUL_FLAG_GENERIC_KERNEL | KRUL_FLAG_SINGLE_SPLIT)) return KRUL_EINVAL;
+    if ((s->flags & KRUL_FLAG_CAUSAL) && s->n_hist < s->n_query) return KRUL_EINVAL;
     if (s->head_dim % 8 != 0 || s->head_dim > 256) return KRUL_EUNSUPPORTED;
     if (s->n_layers > 2048) return KRUL_EUNSUPPORTED;
     return KRUL_OK;
@@ -121,15 +122,18 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__re
 namespace {
 // The one implementation behind the similarity entry points.  ir: also run the Initial-Recent layer
 // test (gamma, ir_mass, eligible as for krul_pair_similarity_ir).
+// accumulate: head_score / pair_dist are the caller's running sums [B][L-1][Hq] (see
+// krul_pair_similarity_accumulate) and pair_score is unused.
 int run_similarity(const krul_shape_t *shape, const void *q, const void *k, float *pair_score,
                    float *head_score, float *pair_dist, bool ir, float gamma, float *ir_mass,
                    uint8_t *eligible, void *workspace, size_t workspace_bytes, void *stream,
-                   void *event_begin, void *event_end)
+                   void *event_begin, void *event_end, bool accumulate = false)
 {
     Plan pl;
     const int rc = make_plan(shape, &pl, ir);
     if (rc != KRUL_OK) return rc;
-    if (!q || !k || !pair_score) return KRUL_EINVAL;
+    if (!q || !k || (accumulate ? !head_score : !pair_score)) return KRUL_EINVAL;
+    if (ir && (shape->flags & KRUL_FLAG_CAUSAL)) return KRUL_EUNSUPPORTED;
     if (((uintptr_t)q | (uintptr_t)k) & 15) return KRUL_EINVAL;
     if (((uintptr_t)pair_score | (uintptr_t)head_score | (uintptr_t)pair_dist | (uintptr_t)ir_mass) & 3)
         return KRUL_EINVAL;
@@ -156,6 +160,7 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     p.c = pl.c;
     p.want_dist = pair_dist != nullptr || ir;   // the test needs Z as well
     p.want_ir = ir;
+    p.causal = (shape->flags & KRUL_FLAG_CAUSAL) != 0;
     // T_initial = T[:10% s], T_recent = T[90% s:] (Sec. 4.2): keys [0, floor(0.1 S)) and [floor(0.9 S), S)
     p.ir_init_end = (int)floor(0.1 * (double)p.S);
     p.ir_recent_begin = (int)floor(0.9 * (double)p.S);
@@ -172,9 +177,9 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     if (event_end && hipEventRecord(static_cast<hipEvent_t>(event_end), st) != hipSuccess)
         return KRUL_ELAUNCH;
     float *head_cos = head_score ? head_score : reinterpret_cast<float *>(ws + pl.head_cos_off);
-    float *head_dist = reinterpret_cast<float *>(ws + pl.head_dist_off);
+    float *head_dist = accumulate ? pair_dist : reinterpret_cast<float *>(ws + pl.head_dist_off);
     e = launch_finalize(pl.lay, p.state, p.B, p.L, p.Hq, p.Hkv, p.Tq, head_cos, head_dist,
-                        pair_score, pair_dist, st);
+                        pair_score, pair_dist, accumulate, st);
     if (e != hipSuccess) return KRUL_ELAUNCH;
     if (ir) {
         e = launch_finalize_ir(pl.lay, p.state, p.state_ir, p.B, p.L, p.Hq, p.Hkv, p.Tq, gamma,
@@ -218,6 +223,30 @@ int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const v
 {
     return run_similarity(shape, q, k, pair_score, head_score, pair_dist, false, 0.f, nullptr, nullptr,
                           workspace, workspace_bytes, stream, event_begin, event_end);
+}
+
+int krul_pair_similarity_accumulate(const krul_shape_t *shape, const void *q, const void *k,
+                                    float *head_sum, float *head_dist_sum,
+                                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_similarity(shape, q, k, nullptr, head_sum, head_dist_sum, false, 0.f, nullptr, nullptr,
+                          workspace, workspace_bytes, stream, nullptr, nullptr, true);
+}
+
+int krul_pair_scores_from_sums(const float *head_sum, const float *head_dist_sum,
+                               int32_t batch, int32_t n_layers, int32_t n_q_heads, float n_tokens,
+                               float *pair_score, float *head_score, float *pair_dist, void *stream)
+{
+    if (!head_sum || !pair_score || batch <= 0 || n_layers < 2 || n_q_heads <= 0 || !(n_tokens > 0.f) ||
+        !isfinite(n_tokens) || (pair_dist && !head_dist_sum))
+        return KRUL_EINVAL;
+    if (((uintptr_t)head_sum | (uintptr_t)head_dist_sum | (uintptr_t)pair_score | (uintptr_t)head_score |
+         (uintptr_t)pair_dist) & 3)
+        return KRUL_EINVAL;
+    const hipError_t e = launch_scores_from_sums(head_sum, head_dist_sum, batch * (n_layers - 1), n_q_heads,
+                                                 1.0f / n_tokens, pair_score, head_score, pair_dist,
+                                                 static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
 }
 
 size_t krul_pair_similarity_ir_workspace(const krul_shape_t *shape)

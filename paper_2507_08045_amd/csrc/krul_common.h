@@ -76,6 +76,7 @@ struct SimParams {
     // Initial-Recent layer test (Sec. 4.2, Alg. 1 first loop): Zir = sum of e over the keys
     // [0, ir_init_end) and [ir_recent_begin, S), one float per record, laid out like state / spill
     int want_ir;
+    int causal;   // row t sees keys j <= S - Tq + t (KRUL_FLAG_CAUSAL)
     int ir_init_end, ir_recent_begin;
     float *state_ir, *spill_ir;
     StateLayout lay;
@@ -84,9 +85,15 @@ struct SimParams {
 // Launchers (each returns hipError_t of the launch).
 hipError_t launch_sim_generic(const SimParams &p, int dtype, int n_workgroups, hipStream_t st);
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st);
+// accumulate: add the sums over rows to head_cos / head_dist (head_dist may then be null) and write no
+// pair scores; otherwise write the means and the pair scores (pair_dist may be null).
 hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, int L, int Hq, int Hkv,
                            int Tq, float *head_cos, float *head_dist, float *pair_cos,
-                           float *pair_dist, hipStream_t st);   // pair_dist may be null
+                           float *pair_dist, bool accumulate, hipStream_t st);
+// head sums -> head and pair scores (head_dist_sum, head_score, pair_dist may be null)
+hipError_t launch_scores_from_sums(const float *head_sum, const float *head_dist_sum, int n_pairs_total,
+                                   int Hq, float inv_tokens, float *pair_cos, float *head_score,
+                                   float *pair_dist, hipStream_t st);
 // Initial-Recent mass per layer from the (m, Z) records and the Zir values: mean over rows and heads of
 // Zir / Z; eligible = (mass >= gamma).  head_ir is scratch [B][L][Hq]; ir_mass or eligible may be null.
 hipError_t launch_finalize_ir(const StateLayout &lay, const float4 *state, const float *state_ir, int B, int L,

@@ -52,7 +52,7 @@ __device__ inline void merge_into(RowAcc &r, float ma, float za, float na, float
 // the same g read consecutive rows, i.e. consecutive records.
 __global__ __launch_bounds__(kThreads) void finalize_heads_kernel(
     StateLayout lay, const float4 *__restrict__ state, int L, int Hq, int Hkv, int Tq, int G,
-    int want_dist, float *__restrict__ head_cos, float *__restrict__ head_dist)
+    int want_dist, int accumulate, float *__restrict__ head_cos, float *__restrict__ head_dist)
 {
     __shared__ float red[kThreads / 64];
     const int NP = L - 1;
@@ -97,21 +97,30 @@ __global__ __launch_bounds__(kThreads) void finalize_heads_kernel(
     const float cs = block_sum(cos_acc, red);
     const float ds = block_sum(dist_acc, red);
     if (threadIdx.x == 0) {
-        head_cos[blockIdx.x] = cs / (float)Tq;
-        head_dist[blockIdx.x] = ds / (float)Tq;
+        if (accumulate) {   // token-wise running sums over several calls (Sec. 5, Sec. 7 "adds up")
+            head_cos[blockIdx.x] += cs;
+            if (want_dist) head_dist[blockIdx.x] += ds;
+        } else {
+            head_cos[blockIdx.x] = cs / (float)Tq;
+            head_dist[blockIdx.x] = ds / (float)Tq;
+        }
     }
 }
 
-__global__ void finalize_pairs_kernel(int n_pairs_total, int Hq, const float *__restrict__ head_cos,
-                                      const float *__restrict__ head_dist,
+// head values times `scale` (1 for means, 1/tokens for running sums): optionally written out as
+// head scores, averaged over the heads in order into the pair scores
+__global__ void finalize_pairs_kernel(int n_pairs_total, int Hq, float scale, const float *__restrict__ head_cos,
+                                      const float *__restrict__ head_dist, float *__restrict__ head_out,
                                       float *__restrict__ pair_cos, float *__restrict__ pair_dist)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_pairs_total) return;
     float cs = 0.f, ds = 0.f;
     for (int h = 0; h < Hq; ++h) {
-        cs += head_cos[(size_t)i * Hq + h];
-        ds += head_dist[(size_t)i * Hq + h];
+        const float c = head_cos[(size_t)i * Hq + h] * scale;
+        if (head_out) head_out[(size_t)i * Hq + h] = c;
+        cs += c;
+        if (pair_dist) ds += head_dist[(size_t)i * Hq + h] * scale;
     }
     pair_cos[i] = cs / (float)Hq;
     if (pair_dist) pair_dist[i] = ds / (float)Hq;
@@ -198,18 +207,27 @@ hipError_t launch_finalize_ir(const StateLayout &lay, const float4 *state, const
 
 hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, int L, int Hq, int Hkv,
                            int Tq, float *head_cos, float *head_dist, float *pair_cos,
-                           float *pair_dist, hipStream_t st)
+                           float *pair_dist, bool accumulate, hipStream_t st)
 {
     const int n_pairs_total = B * (L - 1);
     // lanes per row: enough to keep a workgroup's 256 threads busy, at most one per partial
     int G = 1;
     while (G < 64 && G * Tq < kThreads && G < lay.partials) G <<= 1;
     hipLaunchKernelGGL(finalize_heads_kernel, dim3(n_pairs_total * Hq), dim3(kThreads), 0, st, lay,
-                       state, L, Hq, Hkv, Tq, G, pair_dist != nullptr, head_cos, head_dist);
+                       state, L, Hq, Hkv, Tq, G, pair_dist != nullptr, accumulate ? 1 : 0, head_cos, head_dist);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || accumulate) return e;
     hipLaunchKernelGGL(finalize_pairs_kernel, dim3((n_pairs_total + 127) / 128), dim3(128), 0, st,
-                       n_pairs_total, Hq, head_cos, head_dist, pair_cos, pair_dist);
+                       n_pairs_total, Hq, 1.0f, head_cos, head_dist, (float *)nullptr, pair_cos, pair_dist);
+    return hipGetLastError();
+}
+
+hipError_t launch_scores_from_sums(const float *head_sum, const float *head_dist_sum, int n_pairs_total,
+                                   int Hq, float inv_tokens, float *pair_cos, float *head_score,
+                                   float *pair_dist, hipStream_t st)
+{
+    hipLaunchKernelGGL(finalize_pairs_kernel, dim3((n_pairs_total + 127) / 128), dim3(128), 0, st,
+                       n_pairs_total, Hq, inv_tokens, head_sum, head_dist_sum, head_score, pair_cos, pair_dist);
     return hipGetLastError();
 }
 

@@ -89,7 +89,8 @@ __global__ __launch_bounds__(64) void sim_generic_kernel(SimParams p)
     const int r = (h % p.g) * p.Tq + t;
 
     const int key_begin = sp * p.keys_per_split;
-    const int key_end = min(p.S, key_begin + p.keys_per_split);
+    int key_end = min(p.S, key_begin + p.keys_per_split);
+    if (p.causal) key_end = min(key_end, p.S - p.Tq + t + 1);   // this row sees keys j <= S - Tq + t
 
     for (int l = lane; l < p.L; l += 64) {
         st[l] = make_float4(kMInit, 0.f, 0.f, 0.f);

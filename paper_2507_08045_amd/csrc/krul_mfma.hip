@@ -128,6 +128,8 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
     const int key_begin = sp * p.keys_per_split;
     const int key_end = min(S, key_begin + p.keys_per_split);
+    // causal reading: this lane's query row t (of its head's Tq rows) sees the keys j < row_end
+    const int row_end = p.causal ? S - p.Tq + min(rt * C::R_WG + wr * 32 + l32, Rk - 1) % p.Tq + 1 : S;
     const int ntiles = (key_end - key_begin + C::KT - 1) / C::KT;
     const int nsteps = ntiles * L;          // layer steps; at least 2
     const int nchunks = nsteps * NC;        // at least 4
@@ -291,7 +293,9 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     float rec_ir_pre = 0.f;
     for (int tile = 0; tile < ntiles; ++tile) {
         const int tile_key0 = key_begin + tile * C::KT;
-        const bool ragged = tile_key0 + C::KT > key_end;
+        // keys of this tile to be masked out: past the end of the split, or (causal reading) past
+        // the own position of some row of this wave
+        const bool ragged = tile_key0 + C::KT > key_end || (p.causal && __any(tile_key0 + C::KT > row_end));
         const bool last_tile = tile == ntiles - 1;
 
         for (int l = 0; l < L; ++l, ++step) {
@@ -344,7 +348,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                     // keys at or past key_end: element v of a lane is key kb0 + 8*(v/4) + v%4
 #pragma unroll
                     for (int kb = 0; kb < KBW; ++kb) {
-                        int lim = key_end - (tile_key0 + c * C::CH + (wk * KBW + kb) * 32 + half * 4);
+                        int lim = min(key_end, row_end) - (tile_key0 + c * C::CH + (wk * KBW + kb) * 32 + half * 4);
                         asm volatile("" : "+v"(lim));   // keep the 16 compares here, not hoisted
 #pragma unroll
                         for (int v = 0; v < 16; ++v)

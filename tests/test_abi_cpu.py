@@ -32,7 +32,8 @@ def test_every_declared_symbol_is_exported(kr):
     names = declared_functions()
     assert {"krul_pair_similarity", "krul_select_pairs", "krul_pair_similarity_workspace",
             "krul_n_select_from_ratio", "krul_strerror", "krul_pair_similarity_timed",
-            "krul_pair_similarity_ir", "krul_pair_similarity_ir_workspace"} <= set(names)
+            "krul_pair_similarity_ir", "krul_pair_similarity_ir_workspace",
+            "krul_pair_similarity_accumulate", "krul_pair_scores_from_sums"} <= set(names)
     lib = kr.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in krul.h but not exported"
@@ -70,9 +71,12 @@ def test_workspace_query(kr):
     for name, (B, L, Hq, Hkv, d, S, Tq, dt, _) in workloads.CONFIGS.items():
         assert kr.workspace_bytes(shape(kr, B, L, Hq, Hkv, d, S, Tq, 0 if dt == "f32" else 1)) > 0, name
     bad = [dict(B=0), dict(L=1), dict(Hq=3, Hkv=2), dict(S=0), dict(Tq=0), dict(dtype=7), dict(d=100),
-           dict(d=512), dict(scale=-1.0), dict(scale=float("nan")), dict(flags=1), dict(L=5000)]
+           dict(d=512), dict(scale=-1.0), dict(scale=float("nan")), dict(flags=2), dict(L=5000),
+           dict(flags=1, S=4, Tq=8)]   # causal needs at least as many keys as rows
     for cfg in bad:
         assert kr.workspace_bytes(shape(kr, **cfg)) == 0, cfg
+    assert kr.workspace_bytes(shape(kr, flags=kr.KRUL_FLAG_CAUSAL)) > 0
+    assert kr.workspace_bytes_ir(shape(kr, flags=kr.KRUL_FLAG_CAUSAL)) > 0   # (rejected at the call: see below)
 
 
 def call_sim(kr, shp, q=0x1000, k=0x2000, ps=0x3000, hs=None, pd=None, ws=0x10000, ws_bytes=1 << 40):
@@ -119,6 +123,24 @@ def test_ir_entry_point_rejects_bad_arguments_before_any_gpu_work(kr):
     assert call(ok, mass=0x4002) == kr.KRUL_EINVAL                 # float alignment
     assert call(ok, ws_bytes=need - 1) == kr.KRUL_EWORKSPACE
     assert call(ok, ws_bytes=kr.workspace_bytes(ok)) == kr.KRUL_EWORKSPACE   # the plain call's size is too small
+    assert call(shape(kr, flags=kr.KRUL_FLAG_CAUSAL)) == kr.KRUL_EUNSUPPORTED  # the test is for whole-sequence attention
+
+
+def test_accumulate_entry_points_reject_bad_arguments(kr):
+    vp = ctypes.c_void_p
+    ok = shape(kr)
+    L = kr.lib()
+    assert L.krul_pair_similarity_accumulate(ctypes.byref(ok), vp(0x1000), vp(0x2000), None, None, vp(0x10000),
+                                             ctypes.c_size_t(1 << 40), None) == kr.KRUL_EINVAL
+    assert L.krul_pair_similarity_accumulate(ctypes.byref(ok), vp(0x1000), vp(0x2000), vp(0x3000), None, vp(0x10000),
+                                             ctypes.c_size_t(16), None) == kr.KRUL_EWORKSPACE
+    f = ctypes.c_float
+    assert L.krul_pair_scores_from_sums(None, None, 1, 4, 4, f(8.0), vp(0x3000), None, None, None) == kr.KRUL_EINVAL
+    assert L.krul_pair_scores_from_sums(vp(0x1000), None, 1, 4, 4, f(0.0), vp(0x3000), None, None, None) == kr.KRUL_EINVAL
+    assert L.krul_pair_scores_from_sums(vp(0x1000), None, 1, 1, 4, f(8.0), vp(0x3000), None, None, None) == kr.KRUL_EINVAL
+    assert L.krul_pair_scores_from_sums(vp(0x1000), None, 1, 4, 4, f(8.0), None, None, None, None) == kr.KRUL_EINVAL
+    # a pair distance needs the distance sums
+    assert L.krul_pair_scores_from_sums(vp(0x1000), None, 1, 4, 4, f(8.0), vp(0x3000), None, vp(0x4000), None) == kr.KRUL_EINVAL
 
 
 def test_select_pairs_rejects_bad_arguments(kr):
