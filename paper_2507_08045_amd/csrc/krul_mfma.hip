@@ -127,7 +127,14 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     const int L = p.L, S = p.S, Rk = p.lay.rows_per_unit;
 
     const int key_begin = sp * p.keys_per_split;
-    const int key_end = min(S, key_begin + p.keys_per_split);
+    int key_end = min(S, key_begin + p.keys_per_split);
+    if (p.causal) {
+        // no row of this workgroup sees a key past the last position among its rows: stop there
+        // (at least one key stays, so that every row still gets its -- then empty -- records)
+        const int r_lo = rt * C::R_WG, r_hi = min(r_lo + C::R_WG, Rk) - 1;
+        const int t_max = r_lo / p.Tq != r_hi / p.Tq ? p.Tq - 1 : r_hi % p.Tq;
+        key_end = max(min(key_end, S - p.Tq + t_max + 1), key_begin + 1);
+    }
     // causal reading: this lane's query row t (of its head's Tq rows) sees the keys j < row_end
     const int row_end = p.causal ? S - p.Tq + min(rt * C::R_WG + wr * 32 + l32, Rk - 1) % p.Tq + 1 : S;
     const int ntiles = (key_end - key_begin + C::KT - 1) / C::KT;

@@ -27,6 +27,7 @@ CAUSAL_CASES = [
     ("causal-slim", 1, 5, 4, 1, 128, 2500, 3),
     ("causal-decode", 1, 6, 8, 2, 64, 1111, 1),       # Tq = 1: the mask is empty
     ("causal-tiny", 1, 3, 4, 2, 128, 5, 5),
+    ("causal-long-prefill", 1, 3, 4, 2, 128, 1500, 1500),   # row tiles left of the diagonal skip the keys right of it
 ]
 
 
