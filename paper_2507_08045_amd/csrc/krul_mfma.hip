@@ -1,38 +1,44 @@
 // bf16 MFMA similarity kernel for gfx950 (CDNA4).
 //
 // Work decomposition.  A "unit" is one (conversation, kv head): its (Hq/Hkv)*Tq
-// query rows all read the same keys.  A workgroup (4 or 8 wavefronts) owns R_WG rows of a
-// unit and one contiguous key split; it walks the split in key tiles of KT keys and,
+// query rows all read the same keys.  A workgroup (8 wavefronts, WR x WK) owns R_WG rows
+// of a unit and one contiguous key split; it walks the split in key tiles of KT keys and,
 // inside a tile, the layers 0..L-1 in order, so that every layer's logits are formed
 // exactly once and the previous layer's exponentials of the same keys are still in
 // registers when the cross term (the "ab" of Sec. 7's a^2 + b^2 - 2ab) is taken.
 //
-// K stream.  Per layer step the K tile arrives in NC chunks of CH keys.  Chunks are
-// copied HBM -> LDS by buffer_load_dwordx4 ... lds (no register staging) into a ring of
-// NBUF slots, NBUF-1 chunks ahead of the compute; one s_waitcnt + s_barrier per chunk
-// publishes a slot.  Every slot is its own LDS object and every use names its slot
-// statically, so the compiler can tell a copy in flight from the slot being read and
-// adds no waits of its own.  Inside a slot 16-byte pieces are XOR-swizzled by row so
-// that the 16-byte MFMA operand reads of 16 consecutive rows hit 16 different bank
-// groups (the swizzle is applied on the global side: each lane fetches the piece that
-// belongs in its LDS position).
+// Streams.  A key tile is NC chunks of CH keys; chunk c of a layer step lives in ring slot
+// c.  Chunks, and the next layer's query rows, are copied HBM -> LDS by
+// buffer_load_dwordx4 ... lds (no register staging); the copy issued while chunk c of a
+// step is worked on is chunk c of the next step, i.e. NC-1 chunks ahead.  One count-based
+// s_waitcnt + one s_barrier per chunk publish a slot.  Every slot is its own LDS object
+// and every use names its slot statically, so the compiler can tell a copy in flight
+// from the slot being read and adds no waits of its own.  Inside a slot 16-byte pieces
+// are XOR-swizzled by row so that the 16-byte MFMA operand reads of 16 consecutive rows
+// hit 16 different bank groups (the swizzle is applied on the global side: each lane
+// fetches the piece that belongs in its LDS position).
 //
-// Math.  Per chunk each wave takes KBW blocks of 32 keys and RB blocks of 32 query rows:
+// Math.  Per chunk each wave takes KBW blocks of 32 keys against its 32 query rows:
 //     S^T (32 keys x 32 rows) = K_blk (32 x d) * Q_blk^T (d x 32)
-// with v_mfma_f32_32x32x16_bf16, A = keys (from LDS), B = query rows (registers, loaded
-// once per layer step straight from global memory).  In the result every lane owns ONE
-// query row (column lane%32) and 16 keys, so all softmax reductions are lane-local: no
-// cross-lane traffic in the loop.  Lanes l and l+32 and the WK waves along the keys
-// are independent partials of a row, merged once after the last tile.
+// with v_mfma_f32_32x32x16_bf16, A = keys (from LDS), B = query rows (registers, read once
+// per layer step from their LDS staging area).  In the result every lane owns ONE query
+// row (column lane%32) and 16 keys, so all softmax sums are lane-local: no cross-lane
+// traffic in the loop.  Lanes l and l+32 and the WK waves along the keys are independent
+// partials of a row, merged one step late by the first wave of each wave row.
 //
-// Online softmax uses a lazily updated reference exponent m per (lane, layer): it is
-// raised only when a logit exceeds it by more than kLazy (in log2 units); the running
-// sums Z and N2 are then rescaled.  The exponentials kept for the next layer's cross
-// term are NOT rescaled: each 32-key block remembers the exponent it was formed under,
-// the block's dot product with the next layer is kept apart, and the per-block factors
-// of both layers are applied when the layer step ends.  Cosine and distance are
-// invariant to the choice of m, and e = 2^(x-m) <= 2^kLazy keeps every sum far inside
-// fp32 range.
+// Software pipeline.  While a wave takes the exponentials of chunk c's block it issues the
+// MFMA chain that forms chunk c+1's logits (double-buffered accumulators); the order
+// "one MFMA, the vector work of 16/KS logits, ..." is pinned with empty asm statements.
+//
+// Online softmax uses a reference exponent m per (lane, layer) that is only raised when
+// it has to be: a block is taken under the current m and, if its sum of squares shows an
+// exponential above 2^kLazy (or an overflow), m is raised to the block maximum, the
+// running sums are rescaled and the block is redone.  The exponentials kept for the next
+// layer's cross term are NOT rescaled: each 32-key block remembers the exponent it was
+// formed under, the block's dot product with the next layer is kept apart, and the
+// per-block factors of both layers are applied when the layer step ends.  Cosine and
+// distance are invariant to the choice of m, and e = 2^(x-m) <= 2^kLazy keeps every sum
+// far inside fp32 range.
 #include "krul_common.h"
 
 namespace krul {
