@@ -126,6 +126,32 @@ int krul_pair_similarity_ir(const krul_shape_t *shape, const void *q, const void
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * krul_pair_similarity (same scores: Sec. 5 and Sec. 7) on keys that stay where the inference engine
+ * caches them (the KV caches of Sec. 2.1, which every layer keeps for its own attention): one
+ * allocation per layer and arbitrary strides between conversations, kv heads and keys (e.g. a
+ * [B][S][Hkv][d] cache), so the KV cache of a conversation is scored in place, without a gather.  q is dense as for krul_pair_similarity.
+ *
+ *   k_layers    DEVICE array (8-byte aligned) of n_layers device pointers; k_layers[l] = keys of layer l,
+ *               16-byte aligned.  The array is read by the kernel: it must stay valid and unchanged until
+ *               the call's work on the stream has finished.
+ *   k_stride_b, k_stride_h, k_stride_s
+ *               elements between conversations, kv heads and keys inside a layer: key (b, h, j) starts at
+ *               k_layers[l] + b*k_stride_b + h*k_stride_h + j*k_stride_s; its head_dim elements are
+ *               contiguous.  All > 0 and multiples of 8 elements (k_stride_b is ignored for batch 1),
+ *               k_stride_s >= head_dim (else KRUL_EINVAL); for bf16 with head_dim 64 or 128, k_stride_s must
+ *               be a multiple of head_dim and n_hist * k_stride_s * 2 bytes < 2 GiB (else KRUL_EUNSUPPORTED).
+ * The caller guarantees that every addressed key lies inside its layer's allocation.  Everything else
+ * is as for krul_pair_similarity (same workspace size).
+ */
+typedef struct {
+    const void *const *k_layers;
+    int64_t k_stride_b, k_stride_h, k_stride_s;
+} krul_k_layout_t;
+int krul_pair_similarity_strided(const krul_shape_t *shape, const void *q, const krul_k_layout_t *k_layout,
+                                 float *pair_score, float *head_score, float *pair_dist,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Token-wise accumulation over several calls (Sec. 5 and Sec. 7: the similarities of the tokens of
  * the prefill and of every decode step are added up).  krul_pair_similarity_accumulate adds, for every
  * (conversation, pair, query head), the SUM over this call's n_query rows of the row cosine to

@@ -33,6 +33,11 @@ class KrulShape(ctypes.Structure):
     ]
 
 
+class KrulKLayout(ctypes.Structure):
+    _fields_ = [("k_layers", ctypes.c_void_p), ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64),
+                ("k_stride_s", ctypes.c_int64)]
+
+
 class KrulError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
@@ -63,6 +68,9 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_ir.restype = ctypes.c_int
         L.krul_pair_similarity_ir.argtypes = [ctypes.POINTER(KrulShape), vp, vp, ctypes.c_float, vp, vp, vp, vp, vp,
                                               vp, sz, vp]
+        L.krul_pair_similarity_strided.restype = ctypes.c_int
+        L.krul_pair_similarity_strided.argtypes = [ctypes.POINTER(KrulShape), vp, ctypes.POINTER(KrulKLayout), vp, vp,
+                                                   vp, vp, sz, vp]
         L.krul_pair_similarity_accumulate.restype = ctypes.c_int
         L.krul_pair_similarity_accumulate.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, sz, vp]
         L.krul_pair_scores_from_sums.restype = ctypes.c_int
@@ -158,6 +166,48 @@ def pair_similarity(q: torch.Tensor, k: torch.Tensor, *, scale: float = 0.0, fla
     if rc != KRUL_OK:
         raise KrulError(rc)
     return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace}
+
+
+def pair_similarity_strided(q: torch.Tensor, k_layers, *, scale: float = 0.0, flags: int = 0,
+                            want_head_score: bool = True, want_pair_dist: bool = True,
+                            workspace: torch.Tensor | None = None, k_table: torch.Tensor | None = None) -> dict:
+    """krul_pair_similarity_strided on the current stream.  k_layers: one GPU tensor per layer, each
+    indexed [B, Hkv, S, d] with any strides over the first three axes (the same for every layer) and
+    contiguous head_dim, e.g. cache[l].permute(0, 2, 1, 3) of a [B, S, Hkv, d] cache.  k_table: the
+    device array of the layers' addresses from an earlier call with the same tensors (returned as
+    "k_table"), to skip its upload."""
+    if not q.is_cuda or not all(t.is_cuda for t in k_layers):
+        raise ValueError("q and k must be GPU tensors (this library has no CPU path)")
+    if not q.is_contiguous():
+        raise ValueError("q must be contiguous")
+    k0 = k_layers[0]
+    if q.dim() != 5 or any(t.dim() != 4 or t.shape != k0.shape or t.stride() != k0.stride() or t.dtype != q.dtype
+                           for t in k_layers):
+        raise ValueError("q must be [B,L,Hq,Tq,d] and every k_layers[l] a [B,Hkv,S,d] view of one shape, "
+                         "one set of strides and q's dtype")
+    if k0.stride(3) != 1 or q.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("head_dim must be contiguous; dtype float32 or bfloat16")
+    B, L, Hq, Tq, d = q.shape
+    if len(k_layers) != L or k0.shape[0] != B or k0.shape[3] != d:
+        raise ValueError("q and k disagree on batch, layers or head_dim")
+    shp = KrulShape(B, L, Hq, k0.shape[1], d, k0.shape[2], Tq, KRUL_F32 if q.dtype == torch.float32 else KRUL_BF16,
+                    float(scale), int(flags))
+    if k_table is None:
+        k_table = torch.tensor([t.data_ptr() for t in k_layers], dtype=torch.int64).to(q.device)
+    lay = KrulKLayout(k_table.data_ptr(), k0.stride(0) if B > 1 else 0, k0.stride(1), k0.stride(2))
+    need = workspace_bytes(shp)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ps = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
+    hs = torch.empty((B, L - 1, Hq), dtype=torch.float32, device=q.device) if want_head_score else None
+    pd = torch.empty((B, L - 1), dtype=torch.float32, device=q.device) if want_pair_dist else None
+    rc = lib().krul_pair_similarity_strided(ctypes.byref(shp), _dev_ptr(q), ctypes.byref(lay), _dev_ptr(ps),
+                                            _dev_ptr(hs), _dev_ptr(pd), _dev_ptr(workspace),
+                                            workspace.numel() if workspace is not None else 0,
+                                            ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace, "k_table": k_table}
 
 
 def pair_similarity_ir(q: torch.Tensor, k: torch.Tensor, gamma: float, *, scale: float = 0.0, flags: int = 0,

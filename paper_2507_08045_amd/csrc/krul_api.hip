@@ -127,14 +127,15 @@ namespace {
 int run_similarity(const krul_shape_t *shape, const void *q, const void *k, float *pair_score,
                    float *head_score, float *pair_dist, bool ir, float gamma, float *ir_mass,
                    uint8_t *eligible, void *workspace, size_t workspace_bytes, void *stream,
-                   void *event_begin, void *event_end, bool accumulate = false)
+                   void *event_begin, void *event_end, bool accumulate = false,
+                   const krul_k_layout_t *kl = nullptr)
 {
     Plan pl;
     const int rc = make_plan(shape, &pl, ir);
     if (rc != KRUL_OK) return rc;
-    if (!q || !k || (accumulate ? !head_score : !pair_score)) return KRUL_EINVAL;
+    if (!q || (kl ? !kl->k_layers : !k) || (accumulate ? !head_score : !pair_score)) return KRUL_EINVAL;
     if (ir && (shape->flags & KRUL_FLAG_CAUSAL)) return KRUL_EUNSUPPORTED;
-    if (((uintptr_t)q | (uintptr_t)k) & 15) return KRUL_EINVAL;
+    if (((uintptr_t)q | (uintptr_t)k) & 15 || (kl && ((uintptr_t)kl->k_layers & 7))) return KRUL_EINVAL;
     if (((uintptr_t)pair_score | (uintptr_t)head_score | (uintptr_t)pair_dist | (uintptr_t)ir_mass) & 3)
         return KRUL_EINVAL;
     if (ir && (!(gamma >= 0.f) || !isfinite(gamma) || (!ir_mass && !eligible))) return KRUL_EINVAL;
@@ -167,6 +168,31 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     p.state_ir = reinterpret_cast<float *>(ws + pl.state_ir_off);
     p.spill_ir = reinterpret_cast<float *>(ws + pl.spill_ir_off);
     p.lay = pl.lay;
+    {
+        const long long d = p.d, S = p.S;
+        p.k_tab = nullptr;
+        p.k_stride_l = (long long)p.Hkv * S * d;
+        p.k_stride_b = (long long)p.L * p.Hkv * S * d;
+        p.k_stride_h = S * d;
+        p.k_stride_s = d;
+        if (kl) {
+            const long long sb = p.B > 1 ? kl->k_stride_b : 8;   // (not used for one conversation)
+            if (sb <= 0 || kl->k_stride_h <= 0 || kl->k_stride_s < d || ((sb | kl->k_stride_h | kl->k_stride_s) & 7))
+                return KRUL_EINVAL;
+            // the MFMA kernel's row swizzle needs whole head_dim multiples between keys; its 32-bit
+            // offsets and ranges need a layer's keys of one head to span less than 2 GiB
+            if (pl.lay.variant != kGeneric &&
+                (kl->k_stride_s % d != 0 || kl->k_stride_s * 2 * S >= (1ll << 31)))
+                return KRUL_EUNSUPPORTED;
+            p.k_tab = kl->k_layers;
+            p.k_stride_l = 0;
+            p.k_stride_b = p.B > 1 ? kl->k_stride_b : 0;
+            p.k_stride_h = kl->k_stride_h;
+            p.k_stride_s = kl->k_stride_s;
+        } else if (pl.lay.variant != kGeneric && S * d * 2 >= (1ll << 31)) {
+            return KRUL_EUNSUPPORTED;
+        }
+    }
 
     if (event_begin && hipEventRecord(static_cast<hipEvent_t>(event_begin), st) != hipSuccess)
         return KRUL_ELAUNCH;
@@ -223,6 +249,15 @@ int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const v
 {
     return run_similarity(shape, q, k, pair_score, head_score, pair_dist, false, 0.f, nullptr, nullptr,
                           workspace, workspace_bytes, stream, event_begin, event_end);
+}
+
+int krul_pair_similarity_strided(const krul_shape_t *shape, const void *q, const krul_k_layout_t *k_layout,
+                                 float *pair_score, float *head_score, float *pair_dist,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!k_layout) return KRUL_EINVAL;
+    return run_similarity(shape, q, nullptr, pair_score, head_score, pair_dist, false, 0.f, nullptr, nullptr,
+                          workspace, workspace_bytes, stream, nullptr, nullptr, false, k_layout);
 }
 
 int krul_pair_similarity_accumulate(const krul_shape_t *shape, const void *q, const void *k,

@@ -113,8 +113,9 @@ __global__ __launch_bounds__(64) void sim_generic_kernel(SimParams p)
             __syncthreads();
             float x = -INFINITY;
             if (valid) {
-                const size_t koff = ((((size_t)b * p.L + l) * p.Hkv + kvh) * p.S + key) * p.d;
-                x = dot_row<T>(qs, K + koff, p.d) * p.c;
+                const T *kl = p.k_tab ? static_cast<const T *>(p.k_tab[l]) : K + (size_t)l * p.k_stride_l;
+                const size_t koff = (size_t)b * p.k_stride_b + (size_t)kvh * p.k_stride_h + (size_t)key * p.k_stride_s;
+                x = dot_row<T>(qs, kl + koff, p.d) * p.c;
             }
             const float4 cur = st[l];
             const float m_new = fmaxf(cur.x, wave_max(x));

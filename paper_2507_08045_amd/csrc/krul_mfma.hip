@@ -98,7 +98,15 @@ __device__ inline int swz(int row)
 
 // MODE 0: cosine only; 1: also Z = sum e (needed for the distance); 2: also Zir = sum of e over the
 // initial and recent keys (the Initial-Recent layer test of Sec. 4.2), which needs Z too
-template <class C, int MODE>
+// A wave-uniform address, said to be so: descriptors built from it then stay in scalar registers.
+__device__ inline const uint16_t *uniform_ptr(const uint16_t *ptr)
+{
+    const uintptr_t a = (uintptr_t)ptr;
+    return (const uint16_t *)(((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(a >> 32)) << 32) |
+                              (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a));
+}
+
+template <class C, int MODE, bool SK>
 __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 {
     constexpr int D = C::D, WK = C::WK, KBW = C::KBW, NC = C::NC, KS = C::KS;
@@ -150,8 +158,21 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     const uint16_t *Qg = static_cast<const uint16_t *>(p.q);
     const uint16_t *Kg = static_cast<const uint16_t *>(p.k);
     const size_t q_layer_stride = (size_t)p.Hq * p.Tq * D;
-    const size_t k_layer_stride = (size_t)p.Hkv * S * D;
-    const uint16_t *kbase = Kg + ((size_t)b * L * p.Hkv + kvh) * (size_t)S * D;
+    // Keys of layer l, this unit: k_layer(l) + k_tile_off, where k_tile_off leads to the unit's first key
+    // of the tile being fetched (see SimParams).  Layer and tile advance by additions, so that the dense
+    // layout costs no multiplications inside the loop.
+    const size_t k_stride_s = SK ? (size_t)p.k_stride_s : (size_t)D;   // SK: keys with strides, layers from a table
+    size_t k_tile_off = (size_t)b * p.k_stride_b + (size_t)kvh * p.k_stride_h + (size_t)key_begin * k_stride_s;
+    const size_t k_tile_step = (size_t)C::KT * k_stride_s;
+    const uint16_t *k_dense = Kg;   // dense layout: the layer being fetched starts here
+    auto k_layer = [&](int l) __attribute__((always_inline)) -> const uint16_t * {
+        // the table is read as constant memory at a uniform address: a scalar load, which takes no place in
+        // the vector-memory queue that the ring's waits count
+        typedef const __attribute__((address_space(4))) unsigned long long *const_u64_ptr;
+        return SK ? (const uint16_t *)(uintptr_t)((const_u64_ptr)(uintptr_t)p.k_tab)[l] : k_dense;
+    };
+    const unsigned k_row_bytes = (unsigned)k_stride_s * 2u;   // a multiple of 2*D: the swizzle bits stay clear
+    const unsigned k_chunk_bytes = (unsigned)C::CH * k_row_bytes;   // (a layer's keys of one head span < 2 GiB)
 
     // ---- direct-to-LDS copies.  One wave-instruction moves 1 KB = RPI whole rows: the lane
     // at LDS granule g = row*PPR + pc fetches piece pc ^ swz(row) of its row (the swizzle is
@@ -163,11 +184,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
     // K ring: wave-instruction j of this wave fills granules [(wave*NLD+j)*64, +64) of a slot.
     const int ld_row0 = wave * NLD * RPI + lane / PPR;
-    const unsigned ld_off0 = (unsigned)(ld_row0 * (D * 2) + (((lane % PPR) ^ swz<D>(ld_row0)) * 16));
+    const unsigned ld_off0 = (unsigned)ld_row0 * k_row_bytes + (unsigned)(((lane % PPR) ^ swz<D>(ld_row0)) * 16);
     // The chunk copied during chunk c of a step is chunk c of the NEXT step (PF + 1 = NC chunks
     // later), so per step one base address serves all its copies: that of the next step's
     // layer and key tile (fetch_k), with the tile's first key (fetch_key0).
-    const uint16_t *fetch_k = kbase + (size_t)key_begin * D;
+    const uint16_t *fetch_k = uniform_ptr(k_layer(0) + k_tile_off);
     int fetch_key0 = key_begin;
     auto issue_chunk = [&](int c, bool live) __attribute__((always_inline)) {
         unsigned char *dst = slot_ptr(c);
@@ -175,14 +196,14 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         // Buffer addressing: a scalar descriptor for the rest of this layer's keys (rows past
         // the last key are out of range and are not fetched), one 32-bit offset per lane.
         // (a chunk past the end of the split gets an empty range: nothing is fetched)
-        const unsigned bytes = live ? (unsigned)max(S - key0, 0) * (unsigned)(D * 2) : 0u;
+        const unsigned bytes = live && key0 < S ? (unsigned)(S - key0 - 1) * k_row_bytes + (unsigned)(D * 2) : 0u;
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint16_t *>(fetch_k + c * (C::CH * D)), 0, (int)bytes, 0x00020000);
+            const_cast<uint16_t *>(fetch_k + (c * k_chunk_bytes) / 2), 0, (int)bytes, 0x00020000);
 #pragma unroll
         for (int j = 0; j < NLD; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rsrc, (__attribute__((address_space(3))) void *)(dst + (wave * NLD + j) * 1024), 16,
-                (int)(ld_off0 ^ xj(j)), j * 1024, 0, 0);
+                (int)(ld_off0 ^ xj(j)), (int)(j * RPI * k_row_bytes), 0, 0);
     };
 
     // Query rows: the 32 rows of wave row wr are staged in LDS (laid out like a 32-key block)
@@ -191,12 +212,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     // fetched, their results are never read back.
     const int r0 = rt * C::R_WG + wr * 32;
     const int q_rows = min(max(Rk - r0, 0), 32);
-    const uint16_t *qbase;
-    {   // wave-uniform address: say so, so that the descriptor is built in scalar registers
-        const uintptr_t a = (uintptr_t)(Qg + ((size_t)b * L * p.Hq * p.Tq + (size_t)kvh * Rk + (size_t)(q_rows ? r0 : 0)) * D);
-        qbase = (const uint16_t *)(((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(a >> 32)) << 32) |
-                                   (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a));
-    }
+    const uint16_t *qbase = uniform_ptr(Qg + ((size_t)b * L * p.Hq * p.Tq + (size_t)kvh * Rk + (size_t)(q_rows ? r0 : 0)) * D);
     const unsigned q_off0 = (unsigned)((lane / PPR) * (D * 2) + (((lane % PPR) ^ swz<D>(lane / PPR)) * 16));
     const uint16_t *fetch_q = qbase;   // query rows of the next step's layer
     auto issue_q = [&](bool live) __attribute__((always_inline)) {
@@ -320,7 +336,13 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
             const int ln = l + 1 == L ? 0 : l + 1;
             const int tn_ = l + 1 == L ? tile + 1 : tile;
             fetch_key0 = key_begin + tn_ * C::KT;
-            fetch_k = kbase + (size_t)ln * k_layer_stride + (size_t)fetch_key0 * D;
+            if (l + 1 == L) {
+                k_tile_off += k_tile_step;
+                k_dense = Kg;
+            } else {
+                k_dense += p.k_stride_l;
+            }
+            fetch_k = uniform_ptr(k_layer(ln) + k_tile_off);
             fetch_q = qbase + (size_t)ln * q_layer_stride;
             float mcur = rec.x, tz = 0.f, tn = 0.f;
             float mb[NBLK], dot[NBLK];   // per block: exponent used, dot with previous layer
@@ -521,12 +543,18 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 template <class C>
 hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
 {
-    if (p.want_ir)
-        hipLaunchKernelGGL((sim_mfma_kernel<C, 2>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
+    const dim3 grid(n_workgroups), block(C::THREADS);
+    if (p.k_tab) {   // keys in per-layer allocations, with strides (never with the Initial-Recent test)
+        if (p.want_dist)
+            hipLaunchKernelGGL((sim_mfma_kernel<C, 1, true>), grid, block, 0, st, p);
+        else
+            hipLaunchKernelGGL((sim_mfma_kernel<C, 0, true>), grid, block, 0, st, p);
+    } else if (p.want_ir)
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 2, false>), grid, block, 0, st, p);
     else if (p.want_dist)
-        hipLaunchKernelGGL((sim_mfma_kernel<C, 1>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 1, false>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((sim_mfma_kernel<C, 0>), dim3(n_workgroups), dim3(C::THREADS), 0, st, p);
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 0, false>), grid, block, 0, st, p);
     return hipGetLastError();
 }
 

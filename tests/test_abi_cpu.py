@@ -33,7 +33,8 @@ def test_every_declared_symbol_is_exported(kr):
     assert {"krul_pair_similarity", "krul_select_pairs", "krul_pair_similarity_workspace",
             "krul_n_select_from_ratio", "krul_strerror", "krul_pair_similarity_timed",
             "krul_pair_similarity_ir", "krul_pair_similarity_ir_workspace",
-            "krul_pair_similarity_accumulate", "krul_pair_scores_from_sums"} <= set(names)
+            "krul_pair_similarity_accumulate", "krul_pair_scores_from_sums",
+            "krul_pair_similarity_strided"} <= set(names)
     lib = kr.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in krul.h but not exported"
@@ -124,6 +125,30 @@ def test_ir_entry_point_rejects_bad_arguments_before_any_gpu_work(kr):
     assert call(ok, ws_bytes=need - 1) == kr.KRUL_EWORKSPACE
     assert call(ok, ws_bytes=kr.workspace_bytes(ok)) == kr.KRUL_EWORKSPACE   # the plain call's size is too small
     assert call(shape(kr, flags=kr.KRUL_FLAG_CAUSAL)) == kr.KRUL_EUNSUPPORTED  # the test is for whole-sequence attention
+
+
+def test_strided_entry_point_rejects_bad_arguments_before_any_gpu_work(kr):
+    vp = ctypes.c_void_p
+    ok = shape(kr, B=2)
+
+    def call(shp=ok, tab=0x2000, sb=1 << 20, sh=1 << 16, ss=128, lay=True, ws_bytes=1 << 40):
+        kl = kr.KrulKLayout(tab, sb, sh, ss)
+        return kr.lib().krul_pair_similarity_strided(ctypes.byref(shp), vp(0x1000), ctypes.byref(kl) if lay else None,
+                                                     vp(0x3000), None, None, vp(0x10000), ctypes.c_size_t(ws_bytes),
+                                                     None)
+    assert call(lay=False) == kr.KRUL_EINVAL
+    assert call(tab=None) == kr.KRUL_EINVAL
+    assert call(tab=0x2004) == kr.KRUL_EINVAL          # the table holds 8-byte pointers
+    assert call(sb=0) == kr.KRUL_EINVAL
+    assert call(sh=-128) == kr.KRUL_EINVAL
+    assert call(ss=64) == kr.KRUL_EINVAL               # keys would overlap
+    assert call(ss=132) == kr.KRUL_EINVAL              # not a multiple of 8 elements
+    assert call(ss=136) == kr.KRUL_EUNSUPPORTED        # bf16 kernel: whole head_dims between keys
+    assert call(ss=1 << 23) == kr.KRUL_EUNSUPPORTED    # 256 keys * 16 MiB: beyond the 32-bit key offsets
+    assert call(shape(kr, B=2, flags=kr.KRUL_FLAG_GENERIC_KERNEL), ss=136, ws_bytes=16) == kr.KRUL_EWORKSPACE
+    assert call(shape(kr, B=1), sb=0, ws_bytes=16) == kr.KRUL_EWORKSPACE   # one conversation: k_stride_b unused
+    assert call(shape(kr, Hq=3)) == kr.KRUL_EINVAL
+    assert call(ws_bytes=16) == kr.KRUL_EWORKSPACE
 
 
 def test_accumulate_entry_points_reject_bad_arguments(kr):
