@@ -147,3 +147,41 @@ def ir_mass(q: np.ndarray, k: np.ndarray, gamma: float, scale=None):
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return mass, el
+
+
+def all_pairs(q: np.ndarray, k: np.ndarray, scale=None, causal=False) -> dict:
+    """Similarity of every two layers (Alg. 1 as printed): dict with pair_score, pair_dist [B,L,L]
+    and head_score, head_dist [B,Hq,L,L], float64, symmetric, diagonal cos 1 / distance 0."""
+    q, k, shp = _prep(q, k, scale, causal)
+    B, L, H = shp.batch, shp.n_layers, shp.n_q_heads
+    out = {
+        "pair_score": np.empty((B, L, L)), "pair_dist": np.empty((B, L, L)),
+        "head_score": np.empty((B, H, L, L)), "head_dist": np.empty((B, H, L, L)),
+    }
+    rc = _load().krul_oracle_all_pairs(ctypes.byref(shp), _ptr(q), _ptr(k), _ptr(out["pair_score"]),
+                                       _ptr(out["pair_dist"]), _ptr(out["head_score"]), _ptr(out["head_dist"]))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return out
+
+
+def select_pairs_all(score, n_select: int, closer_is_smaller: bool, eligible=None):
+    """Greedy disjoint choice over every two layers (Alg. 1).  score [B,L,L] (lower triangle read) ->
+    (pairs [B,n_select,2] int32 as (j, i), j < i, padded with -1; count [B] int32)."""
+    sc = np.ascontiguousarray(np.asarray(score, dtype=np.float64))
+    if sc.ndim == 2:
+        sc = sc[None]
+    B, L, L2 = sc.shape
+    if L != L2:
+        raise ValueError("score must be [B,L,L]")
+    el = None
+    if eligible is not None:
+        el = np.ascontiguousarray(np.asarray(eligible, dtype=np.uint8).reshape(B, L))
+    pairs = np.empty((B, max(n_select, 0), 2), dtype=np.int32)
+    count = np.empty((B,), dtype=np.int32)
+    rc = _load().krul_oracle_select_pairs_all(
+        _ptr(sc), ctypes.c_int(1 if closer_is_smaller else 0), _ptr(el) if el is not None else None,
+        ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(n_select), _ptr(pairs), _ptr(count))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return pairs, count

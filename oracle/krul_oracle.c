@@ -21,7 +21,10 @@
  *   - the greedy disjoint pair choice of Alg. 1 (sort by similarity, skip a pair
  *     if either layer is already shared, stop at the budget) (Sec. 4.2);
  *   - the input-insensitive ("I-R") layer test of Sec. 4.2 / Alg. 1, first loop:
- *     mean attention mass on the first and last tenth of the history.
+ *     mean attention mass on the first and last tenth of the history;
+ *   - the same similarities and the same greedy choice over EVERY two layers
+ *     i > j, as Alg. 1 is printed (krul_oracle_all_pairs,
+ *     krul_oracle_select_pairs_all).
  *
  * Readings taken where the paper leaves a choice (adjacent pairs only, row-wise
  * similarity then mean, grouped-query head mapping h -> h / (Hq/Hkv), no mask
@@ -317,6 +320,146 @@ int krul_oracle_ir_mass(const oracle_shape_t *s, const void *q, const void *k,
         if (eligible) eligible[bl] = (uint8_t)(m >= gamma);
     }
     free(unit_mass);
+    return 0;
+}
+
+/*
+ * Alg. 1 as printed scores EVERY two layers i > j, not only neighbours ("for every two weights
+ * A_i, A_j (i > j)", Sec. 4.2; the similarity figure of Sec. 2.3 shows the full layer-by-layer
+ * map).  For every conversation b, query head h and layers i != j: the mean over the query rows
+ * of the cosine similarity and of the Euclidean distance between the rows that layers i and j
+ * give the same token; then the average over heads.
+ *   head_cos / head_dist : [B][Hq][L][L]   (may be NULL)
+ *   pair_cos / pair_dist : [B][L][L]       (may be NULL)
+ * All are symmetric; the diagonal holds cos 1 and distance 0 (a row against itself).
+ */
+int krul_oracle_all_pairs(const oracle_shape_t *s, const void *q, const void *k,
+                          double *pair_cos, double *pair_dist, double *head_cos, double *head_dist)
+{
+    if (!shape_ok(s) || !q || !k)
+        return -1;
+    const int B = s->batch, L = s->n_layers, H = s->n_q_heads, S = s->n_hist, Tq = s->n_query;
+    const size_t LL = (size_t)L * L;
+    double *hc = (double *)malloc(sizeof(double) * (size_t)B * H * LL);
+    double *hd = (double *)malloc(sizeof(double) * (size_t)B * H * LL);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        const int b = bh / H, h = bh % H;
+        /* the attention weights of all layers for this head, stored: P[l][t][j] */
+        double *P = (double *)malloc(sizeof(double) * (size_t)L * Tq * S);
+        for (int l = 0; l < L; ++l)
+            attention_weights(s, q, k, b, l, h, P + (size_t)l * Tq * S);
+        double *c_out = hc + (size_t)bh * LL, *d_out = hd + (size_t)bh * LL;
+        for (int i = 0; i < L; ++i) {
+            c_out[(size_t)i * L + i] = 1.0;
+            d_out[(size_t)i * L + i] = 0.0;
+            for (int j = 0; j < i; ++j) {
+                double csum = 0.0, dsum = 0.0;
+                for (int t = 0; t < Tq; ++t) {
+                    const double *a = P + ((size_t)i * Tq + t) * S;
+                    const double *c = P + ((size_t)j * Tq + t) * S;
+                    double ab = 0.0, aa = 0.0, bb = 0.0, dd = 0.0;
+                    for (int x = 0; x < S; ++x) {
+                        ab += a[x] * c[x];
+                        aa += a[x] * a[x];
+                        bb += c[x] * c[x];
+                        const double df = a[x] - c[x];
+                        dd += df * df;
+                    }
+                    csum += ab / (sqrt(aa) * sqrt(bb));
+                    dsum += sqrt(dd);
+                }
+                c_out[(size_t)i * L + j] = c_out[(size_t)j * L + i] = csum / Tq;
+                d_out[(size_t)i * L + j] = d_out[(size_t)j * L + i] = dsum / Tq;
+            }
+        }
+        free(P);
+    }
+    for (int b = 0; b < B; ++b)
+        for (size_t e = 0; e < LL; ++e) {
+            double cs = 0.0, ds = 0.0;
+            for (int h = 0; h < H; ++h) {
+                cs += hc[((size_t)b * H + h) * LL + e];
+                ds += hd[((size_t)b * H + h) * LL + e];
+            }
+            if (pair_cos) pair_cos[(size_t)b * LL + e] = cs / H;
+            if (pair_dist) pair_dist[(size_t)b * LL + e] = ds / H;
+        }
+    if (head_cos) memcpy(head_cos, hc, sizeof(double) * (size_t)B * H * LL);
+    if (head_dist) memcpy(head_dist, hd, sizeof(double) * (size_t)B * H * LL);
+    free(hc);
+    free(hd);
+    return 0;
+}
+
+/*
+ * Alg. 1, second half (Sec. 4.2), over every two layers i > j.  score[b][i][j] (the lower
+ * triangle of an [L][L] matrix is read) measures the two layers: a distance (closer_is_smaller
+ * != 0: Alg. 1's "Euclidean_Distance", taken in ascending order) or a similarity
+ * (closer_is_smaller == 0: taken in descending order).  A pair is a candidate only if both its
+ * layers are eligible (eligible == NULL: all are).  Candidates are listed with j ascending,
+ * then i ascending, stably ordered by score and scanned once; a pair is taken iff neither of its
+ * layers has been taken; the scan stops once n_select pairs are held.
+ * out_pairs[b][n][2] = (j, i) with j < i, in the order chosen; (-1, -1) beyond out_count[b].
+ */
+int krul_oracle_select_pairs_all(const double *score, int closer_is_smaller, const uint8_t *eligible,
+                                 int batch, int n_layers, int n_select,
+                                 int32_t *out_pairs, int32_t *out_count)
+{
+    if (!score || batch <= 0 || n_layers < 2 || n_select < 0 || !out_count ||
+        (n_select > 0 && !out_pairs))
+        return -1;
+    const int L = n_layers;
+    const int NC = L * (L - 1) / 2;
+    int *cj = (int *)malloc(sizeof(int) * (size_t)NC), *ci = (int *)malloc(sizeof(int) * (size_t)NC);
+    double *key = (double *)malloc(sizeof(double) * (size_t)NC);
+    uint8_t *shared = (uint8_t *)malloc((size_t)L);
+    for (int b = 0; b < batch; ++b) {
+        const double *sc = score + (size_t)b * L * L;
+        const uint8_t *el = eligible ? eligible + (size_t)b * L : NULL;
+        int n = 0;
+        for (int j = 0; j < L; ++j)
+            for (int i = j + 1; i < L; ++i)
+                if (!el || (el[i] && el[j])) {
+                    cj[n] = j;
+                    ci[n] = i;
+                    /* one ordering for both readings: ascending key */
+                    key[n] = closer_is_smaller ? sc[(size_t)i * L + j] : -sc[(size_t)i * L + j];
+                    ++n;
+                }
+        /* stable insertion sort, ascending key */
+        for (int a = 1; a < n; ++a) {
+            const int tj = cj[a], ti = ci[a];
+            const double tk = key[a];
+            int p = a - 1;
+            while (p >= 0 && key[p] > tk) {
+                cj[p + 1] = cj[p];
+                ci[p + 1] = ci[p];
+                key[p + 1] = key[p];
+                --p;
+            }
+            cj[p + 1] = tj;
+            ci[p + 1] = ti;
+            key[p + 1] = tk;
+        }
+        memset(shared, 0, (size_t)L);
+        int cnt = 0;
+        for (int a = 0; a < n && cnt < n_select; ++a) {
+            if (shared[ci[a]] || shared[cj[a]])
+                continue;
+            shared[ci[a]] = shared[cj[a]] = 1;
+            out_pairs[((size_t)b * n_select + cnt) * 2] = cj[a];
+            out_pairs[((size_t)b * n_select + cnt) * 2 + 1] = ci[a];
+            ++cnt;
+        }
+        out_count[b] = cnt;
+        for (int a = cnt; a < n_select; ++a)
+            out_pairs[((size_t)b * n_select + a) * 2] = out_pairs[((size_t)b * n_select + a) * 2 + 1] = -1;
+    }
+    free(cj);
+    free(ci);
+    free(key);
+    free(shared);
     return 0;
 }
 
