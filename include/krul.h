@@ -208,6 +208,52 @@ int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
                       int32_t *out_pairs, int32_t *out_count, void *stream);
 
 /*
+ * Similarity of EVERY two layers i > j, as Alg. 1 is printed ("for every two weights A_i, A_j (i > j)",
+ * Sec. 4.2; the layer-by-layer similarity map of Sec. 2.3), not only of neighbours.  Same definitions as
+ * krul_pair_similarity: per conversation, query head and query row the cosine and the Euclidean distance
+ * between the attention rows that layers i and j give the row; mean over rows (Sec. 5, Sec. 7), then the
+ * average over heads (Sec. 4.2).
+ *
+ *   q, k            as for krul_pair_similarity (dense layouts); KRUL_FLAG_CAUSAL is honoured
+ *   pair_score_all  [B][L][L] float   device: mean cosine of layers i and j at [i][j] and [j][i]; 1 on the diagonal
+ *   pair_dist_all   [B][L][L] float   device, may be NULL: mean distance, 0 on the diagonal
+ *   head_score_all  [B][Hq][L][L] float  device, may be NULL: the cosines before the average over heads
+ *   workspace       device, 256-byte aligned.  The attention weights of a batch of query rows are kept
+ *                   in it (fp16), as the paper keeps them (Sec. 5), so its size sets how many rows one
+ *                   batch holds: krul_all_pairs_workspace(shape, max_bytes) returns the bytes for the
+ *                   largest batch that fits max_bytes (max_bytes 0: a default budget of 2 GiB; never
+ *                   less than the bytes for the smallest batch, 128 rows of one kv head), or 0 if the
+ *                   shape is not supported.  Any size from the smallest batch's up is accepted by the
+ *                   call; more memory means fewer, larger launches.
+ * Limits: n_layers <= 128.  bf16 with head_dim 64 or 128 runs on the matrix cores; other inputs take a
+ * portable, slow kernel.  Exponentials are rounded to fp16 (2^-11 relative) before the products.
+ * Results are deterministic.  Errors as for krul_pair_similarity.
+ */
+size_t krul_all_pairs_workspace(const krul_shape_t *shape, size_t max_bytes);
+int krul_all_pairs_similarity(const krul_shape_t *shape, const void *q, const void *k,
+                              float *pair_score_all, float *pair_dist_all, float *head_score_all,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Greedy disjoint pair selection over every two layers (Alg. 1 second loop as printed; Sec. 4.2).
+ * Candidates are the pairs (j, i), j < i, of eligible layers, scored by score[b][i][j] (only the
+ * entries below the diagonal are read).  closer_is_smaller != 0: the score is a distance, taken in
+ * ascending order (Alg. 1's Euclidean distance); 0: a similarity, taken in descending order.  Equal
+ * scores: lower j first, then lower i.  A pair is taken iff neither of its layers is in a taken pair;
+ * the scan stops at n_select pairs.
+ *
+ *   score      [B][n_layers][n_layers] float   device (e.g. pair_dist_all or pair_score_all)
+ *   eligible   [B][n_layers] uint8             device, or NULL = every layer eligible
+ *   out_pairs  [B][n_select][2] int32          device: (j, i) of each taken pair in the order taken,
+ *                                              (-1, -1) after out_count[b]
+ *   out_count  [B] int32                       device
+ * Limits: 2 <= n_layers <= 4096, 0 <= n_select <= n_layers/2.
+ */
+int krul_select_pairs_all(const float *score, int32_t closer_is_smaller, const uint8_t *eligible,
+                          int32_t batch, int32_t n_layers, int32_t n_select,
+                          int32_t *out_pairs, int32_t *out_count, void *stream);
+
+/*
  * Pairs to select for a compression ratio r_l: Alg. 1 stops once the shared-layer
  * set holds N * r_l layers, two per pair, so ceil(N * r_l / 2), clamped to
  * [0, N/2].  Host-only.

@@ -75,6 +75,12 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_accumulate.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, sz, vp]
         L.krul_pair_scores_from_sums.restype = ctypes.c_int
         L.krul_pair_scores_from_sums.argtypes = [vp, vp, i32, i32, i32, ctypes.c_float, vp, vp, vp, vp]
+        L.krul_all_pairs_workspace.restype = sz
+        L.krul_all_pairs_workspace.argtypes = [ctypes.POINTER(KrulShape), sz]
+        L.krul_all_pairs_similarity.restype = ctypes.c_int
+        L.krul_all_pairs_similarity.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.krul_select_pairs_all.restype = ctypes.c_int
+        L.krul_select_pairs_all.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp, vp]
         L.krul_select_pairs.restype = ctypes.c_int
         L.krul_select_pairs.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
         L.krul_calibration_copy.restype = ctypes.c_int
@@ -301,6 +307,63 @@ def select_pairs(pair_score: torch.Tensor, n_select: int, eligible: torch.Tensor
         out_count = torch.empty((B,), dtype=torch.int32, device=pair_score.device)
     rc = lib().krul_select_pairs(_dev_ptr(pair_score), _dev_ptr(eligible), B, L, int(n_select),
                                  _dev_ptr(out_pairs), _dev_ptr(out_count), ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return out_pairs, out_count
+
+
+def all_pairs_workspace_bytes(shape: KrulShape, max_bytes: int = 0) -> int:
+    return int(lib().krul_all_pairs_workspace(ctypes.byref(shape), int(max_bytes)))
+
+
+def all_pairs_similarity(q: torch.Tensor, k: torch.Tensor, *, scale: float = 0.0, flags: int = 0,
+                         want_pair_dist: bool = True, want_head_score: bool = False,
+                         workspace: torch.Tensor | None = None, max_workspace_bytes: int = 0) -> dict:
+    """krul_all_pairs_similarity on the current stream.  Returns device tensors pair_score [B,L,L],
+    pair_dist [B,L,L] (or None), head_score [B,Hq,L,L] (or None) and the workspace used."""
+    if not (q.is_cuda and k.is_cuda):
+        raise ValueError("q and k must be GPU tensors (this library has no CPU path)")
+    if not (q.is_contiguous() and k.is_contiguous()):
+        raise ValueError("q and k must be contiguous")
+    shp = make_shape(q, k, scale, flags)
+    B, L, Hq = shp.batch, shp.n_layers, shp.n_q_heads
+    if workspace is None:
+        need = all_pairs_workspace_bytes(shp, max_workspace_bytes)
+        if need == 0:   # let the library name the reason
+            rc = lib().krul_all_pairs_similarity(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), None, None, None,
+                                                 None, 0, None)
+            raise KrulError(rc if rc != 0 else KRUL_EINVAL)
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ps = torch.empty((B, L, L), dtype=torch.float32, device=q.device)
+    pd = torch.empty((B, L, L), dtype=torch.float32, device=q.device) if want_pair_dist else None
+    hs = torch.empty((B, Hq, L, L), dtype=torch.float32, device=q.device) if want_head_score else None
+    rc = lib().krul_all_pairs_similarity(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), _dev_ptr(ps), _dev_ptr(pd),
+                                         _dev_ptr(hs), _dev_ptr(workspace), workspace.numel(),
+                                         ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return {"pair_score": ps, "pair_dist": pd, "head_score": hs, "workspace": workspace}
+
+
+def select_pairs_all(score: torch.Tensor, n_select: int, closer_is_smaller: bool,
+                     eligible: torch.Tensor | None = None):
+    """krul_select_pairs_all on the current stream: (pairs [B,n_select,2] int32 as (j, i), count [B] int32)."""
+    if not score.is_cuda or score.dtype != torch.float32 or not score.is_contiguous():
+        raise ValueError("score must be a contiguous float32 GPU tensor")
+    if score.dim() == 2:
+        score = score[None]
+    B, L, L2 = score.shape
+    if L != L2:
+        raise ValueError("score must be [B, n_layers, n_layers]")
+    if eligible is not None:
+        if not eligible.is_cuda or eligible.dtype != torch.uint8 or tuple(eligible.shape) != (B, L) \
+                or not eligible.is_contiguous():
+            raise ValueError("eligible must be a contiguous uint8 GPU tensor [B, n_layers]")
+    out_pairs = torch.empty((B, max(int(n_select), 0), 2), dtype=torch.int32, device=score.device)
+    out_count = torch.empty((B,), dtype=torch.int32, device=score.device)
+    rc = lib().krul_select_pairs_all(_dev_ptr(score), 1 if closer_is_smaller else 0, _dev_ptr(eligible), B, L,
+                                     int(n_select), _dev_ptr(out_pairs), _dev_ptr(out_count),
+                                     ctypes.c_void_p(_stream_ptr()))
     if rc != KRUL_OK:
         raise KrulError(rc)
     return out_pairs, out_count

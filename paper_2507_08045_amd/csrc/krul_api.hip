@@ -12,6 +12,8 @@ constexpr size_t kAlign = 256;
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+}  // namespace
+
 int check_shape(const krul_shape_t *s)
 {
     if (!s) return KRUL_EINVAL;
@@ -28,7 +30,6 @@ int check_shape(const krul_shape_t *s)
     return KRUL_OK;
 }
 
-}  // namespace
 
 int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
 {
@@ -258,6 +259,33 @@ int krul_pair_similarity_strided(const krul_shape_t *shape, const void *q, const
     if (!k_layout) return KRUL_EINVAL;
     return run_similarity(shape, q, nullptr, pair_score, head_score, pair_dist, false, 0.f, nullptr, nullptr,
                           workspace, workspace_bytes, stream, nullptr, nullptr, false, k_layout);
+}
+
+size_t krul_all_pairs_workspace(const krul_shape_t *shape, size_t max_bytes)
+{
+    return all_pairs_workspace(shape, max_bytes);
+}
+
+int krul_all_pairs_similarity(const krul_shape_t *shape, const void *q, const void *k,
+                              float *pair_score_all, float *pair_dist_all, float *head_score_all,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_all_pairs(shape, q, k, pair_score_all, pair_dist_all, head_score_all, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(stream));
+}
+
+int krul_select_pairs_all(const float *score, int32_t closer_is_smaller, const uint8_t *eligible,
+                          int32_t batch, int32_t n_layers, int32_t n_select,
+                          int32_t *out_pairs, int32_t *out_count, void *stream)
+{
+    if (!score || !out_count || batch <= 0 || n_layers < 2 || n_select < 0 || n_select > n_layers / 2 ||
+        (n_select > 0 && !out_pairs))
+        return KRUL_EINVAL;
+    if (((uintptr_t)score | (uintptr_t)out_pairs | (uintptr_t)out_count) & 3) return KRUL_EINVAL;
+    if (n_layers > 4096) return KRUL_EUNSUPPORTED;
+    const hipError_t e = launch_select_all(score, closer_is_smaller, eligible, batch, n_layers, n_select, out_pairs,
+                                           out_count, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
 }
 
 int krul_pair_similarity_accumulate(const krul_shape_t *shape, const void *q, const void *k,

@@ -87,6 +87,18 @@ struct SimParams {
     StateLayout lay;
 };
 
+// Host: shape checks common to all entry points.  Returns a krul_status_t.
+int check_shape(const krul_shape_t *s);
+
+// Similarity of every two layers (krul_allpairs.hip).  all_pairs_workspace: bytes for the largest batch
+// of rows that fits max_bytes (0: a default budget), 0 if the shape is not supported.  run_all_pairs
+// validates, enqueues everything on st and returns a krul_status_t.
+size_t all_pairs_workspace(const krul_shape_t *s, size_t max_bytes);
+int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pair_score, float *pair_dist,
+                  float *head_score, void *workspace, size_t workspace_bytes, hipStream_t st);
+hipError_t launch_select_all(const float *score, int closer_is_smaller, const uint8_t *eligible, int batch,
+                             int n_layers, int n_select, int32_t *out_pairs, int32_t *out_count, hipStream_t st);
+
 // Launchers (each returns hipError_t of the launch).
 hipError_t launch_sim_generic(const SimParams &p, int dtype, int n_workgroups, hipStream_t st);
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st);

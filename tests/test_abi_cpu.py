@@ -34,7 +34,8 @@ def test_every_declared_symbol_is_exported(kr):
             "krul_n_select_from_ratio", "krul_strerror", "krul_pair_similarity_timed",
             "krul_pair_similarity_ir", "krul_pair_similarity_ir_workspace",
             "krul_pair_similarity_accumulate", "krul_pair_scores_from_sums",
-            "krul_pair_similarity_strided"} <= set(names)
+            "krul_pair_similarity_strided", "krul_all_pairs_similarity", "krul_all_pairs_workspace",
+            "krul_select_pairs_all"} <= set(names)
     lib = kr.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in krul.h but not exported"
@@ -166,6 +167,47 @@ def test_accumulate_entry_points_reject_bad_arguments(kr):
     assert L.krul_pair_scores_from_sums(vp(0x1000), None, 1, 4, 4, f(8.0), None, None, None, None) == kr.KRUL_EINVAL
     # a pair distance needs the distance sums
     assert L.krul_pair_scores_from_sums(vp(0x1000), None, 1, 4, 4, f(8.0), vp(0x3000), None, vp(0x4000), None) == kr.KRUL_EINVAL
+
+
+def test_all_pairs_entry_points_reject_bad_arguments_before_any_gpu_work(kr):
+    vp = ctypes.c_void_p
+    ok = shape(kr)
+    full = kr.all_pairs_workspace_bytes(ok)
+    one = kr.all_pairs_workspace_bytes(ok, 1)
+    assert 0 < one <= full and full % 256 == 0
+    assert kr.all_pairs_workspace_bytes(shape(kr, L=129)) == 0          # at most 128 layers
+    assert kr.all_pairs_workspace_bytes(shape(kr, Hq=3)) == 0
+    assert kr.all_pairs_workspace_bytes(shape(kr, dtype=0, d=72)) > 0    # portable kernel
+    # the batch grows with the budget, up to all rows
+    big = shape(kr, B=2, L=32, Hq=32, Hkv=8, S=4096, Tq=64)
+    sizes = [kr.all_pairs_workspace_bytes(big, m) for m in (1, 1 << 27, 1 << 29, 1 << 40)]
+    assert sizes == sorted(sizes) and sizes[0] < sizes[-1] and sizes[1] <= 1 << 27 and sizes[2] <= 1 << 29
+
+    def call(shp=ok, q=0x1000, k=0x2000, ps=0x3000, ws=0x10000, ws_bytes=1 << 40):
+        return kr.lib().krul_all_pairs_similarity(ctypes.byref(shp), vp(q), vp(k), vp(ps), None, None, vp(ws),
+                                                  ctypes.c_size_t(ws_bytes), None)
+    assert call(shape(kr, L=1)) == kr.KRUL_EINVAL
+    assert call(shape(kr, L=200)) == kr.KRUL_EUNSUPPORTED
+    assert call(shape(kr, dtype=5)) == kr.KRUL_EDTYPE
+    assert call(q=None) == kr.KRUL_EINVAL
+    assert call(ps=None) == kr.KRUL_EINVAL
+    assert call(k=0x2008) == kr.KRUL_EINVAL
+    assert call(ws=None) == kr.KRUL_EWORKSPACE
+    assert call(ws=0x10010) == kr.KRUL_EWORKSPACE
+    assert call(ws_bytes=one - 1) == kr.KRUL_EWORKSPACE
+
+    f = kr.lib().krul_select_pairs_all
+
+    def sel(sc=0x1000, B=1, L=8, n=2, op=0x2000, oc=0x3000):
+        return f(vp(sc), 1, None, B, L, n, vp(op), vp(oc), None)
+    assert sel(sc=None) == kr.KRUL_EINVAL
+    assert sel(oc=None) == kr.KRUL_EINVAL
+    assert sel(op=None) == kr.KRUL_EINVAL
+    assert sel(B=0) == kr.KRUL_EINVAL
+    assert sel(L=1) == kr.KRUL_EINVAL
+    assert sel(n=5) == kr.KRUL_EINVAL
+    assert sel(L=5000, n=1) == kr.KRUL_EUNSUPPORTED
+    assert sel(sc=0x1002) == kr.KRUL_EINVAL
 
 
 def test_select_pairs_rejects_bad_arguments(kr):
