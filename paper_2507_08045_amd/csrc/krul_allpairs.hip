@@ -42,8 +42,8 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int kRowsPerGroup = 128;   // rows of one weights-kernel workgroup: four 32-row blocks
 constexpr int kThreads = 256;
+constexpr int kKeysPerSplit = 256;   // keys of one weights-kernel workgroup (held in LDS)
 
 struct APParams {
     const void *q;
@@ -51,13 +51,20 @@ struct APParams {
     int B, L, Hq, Hkv, g, d, S, Tq, Rk;
     int causal;
     float c;            // scale * log2(e)
-    int NRG;            // 128-row groups per unit
+    int NW;             // 32-row blocks per row group = waves of a weights-kernel workgroup (1, 2 or 4)
+    int NRG;            // row groups per unit
     int NKB;            // 32-key blocks per row
+    int NKBs;           // ... and the stride between layers in E, in blocks: odd, so that the layers' streams
+                        // of one key block do not all fall on the same memory channel
+    int nsplit, kps;    // key splits of the weights kernel, keys per split (a multiple of 32)
     int grg0, nrg;      // this batch: global row groups [grg0, grg0 + nrg)
     int want_dist;
-    unsigned char *E;   // [nrg*4][L][NKB][32][64 bytes]
-    float *rowZ;        // [nrg*128][L]
-    float *row_cos;     // [nrg*128][L*L]  (entries i > j)
+    unsigned char *E;   // [nrg*NW][L][NKBs][32][64 bytes]; e = 2^(x - m) with m of the row, layer and key split
+    float *rowM;        // [nrg*NW*32][nsplit][L]  reference exponent m; then the factor 2^(m - largest m of the row, layer)
+    float *rowZ;        // [nrg*NW*32][nsplit][L]  sum of e over the split's keys
+    float *rowZt;       // [nrg*NW*32][L]          1 / (sum of e over all keys, at the common exponent)
+    float *Gpart;       // [nrg*NW*32][ksp][NACC*1024] partial Gram matrices, result-register order
+    float *row_cos;     // [nrg*NW*32][L*L]  (entries i > j)
     float *row_dist;    // same, or unused
     float *head_cos;    // [B][Hq][L*L] running sums over the rows of a head
     float *head_dist;
@@ -65,7 +72,7 @@ struct APParams {
 
 __device__ inline size_t e_block_offset(const APParams &p, int rbl, int l, int kb)
 {
-    return ((((size_t)rbl * p.L + l) * p.NKB + kb) * 32) * 64;
+    return ((((size_t)rbl * p.L + l) * p.NKBs + kb) * 32) * 64;
 }
 
 // Row-dependent XOR applied to the 16-byte piece index inside an LDS tile of key rows, so that the
@@ -84,26 +91,51 @@ __device__ inline uint32_t pack_f16(float a, float b)
 
 // ------------------------------------------------------------------------------------------------
 // 1. weights kernel (bf16, head_dim 64 or 128)
-template <int D>
-__global__ __launch_bounds__(kThreads) void ap_weights_mfma_kernel(APParams p)
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) void ap_weights_mfma_kernel(APParams p)
 {
-    constexpr int KS = D / 16, PPR = D / 8, ROWB = D * 2, CHK = 64, SLOT = CHK * ROWB;
-    constexpr int NLD = CHK * PPR / kThreads;
-    __shared__ __attribute__((aligned(16))) unsigned char kl[2][SLOT];
+    constexpr int KS = D / 16, PPR = D / 8, ROWB = D * 2, KR = kKeysPerSplit;
+    __shared__ __attribute__((aligned(16))) unsigned char kl[KR * ROWB];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, n = lane & 31;
-    const int l = blockIdx.x % p.L;
-    const int rgl = blockIdx.x / p.L;
+    const int sp = blockIdx.x % p.nsplit;
+    const int l = (blockIdx.x / p.nsplit) % p.L;
+    const int rgl = blockIdx.x / (p.nsplit * p.L);
     const int grg = p.grg0 + rgl;
     const int u = grg / p.NRG, rg = grg % p.NRG;
     const int b = u / p.Hkv, kvh = u % p.Hkv;
-    const int rbl = rgl * 4 + w;
-    const int r = (rg * 4 + w) * 32 + n;            // row of the unit: head-in-group * Tq + t
-    const bool blk_ok = (rg * 4 + w) * 32 < p.Rk;   // this wave has rows at all
+    const int rbl = rgl * NW + w;
+    const int r = (rg * NW + w) * 32 + n;            // row of the unit: head-in-group * Tq + t
+    const bool blk_ok = (rg * NW + w) * 32 < p.Rk;   // this wave has rows at all
     const bool row_ok = r < p.Rk;
     const int S = p.S;
     const int row_end = row_ok ? (p.causal ? S - p.Tq + r % p.Tq + 1 : S) : 0;   // keys [0, row_end) are seen
 
+    // This workgroup's keys [k0, k0 + kn) are copied HBM -> LDS once, by buffer_load ... lds (no
+    // register staging): wave-instruction j fills the 1 KB at j*1024 (RPI key rows), lane by lane,
+    // so each lane fetches the 16-byte piece that belongs at its LDS position (the XOR swizzle is
+    // applied on the global side); rows past kn are out of the descriptor's range and read as zero.
+    constexpr int RPI = 64 / PPR, NI = KR / RPI / NW;
+    const int k0 = sp * KR, kn = min(KR, S - k0);
+    const uint16_t *kbase = static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S + k0) * D;
+    auto copy_keys = [&]() __attribute__((always_inline)) {
+#if defined(__HIP_DEVICE_COMPILE__)   // (the host pass only needs the kernel's launch stub)
+        const uintptr_t ka = (uintptr_t)kbase;   // wave-uniform: keep the descriptor in scalar registers
+        const uint16_t *kb_u = (const uint16_t *)(((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(ka >> 32)) << 32) |
+                                                  (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)ka));
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(kb_u), 0, __builtin_amdgcn_readfirstlane(kn * ROWB), 0x00020000);
+#pragma unroll
+        for (int jj = 0; jj < NI; ++jj) {
+            const int j = w * NI + jj;
+            const int row = j * RPI + lane / PPR, pos = lane % PPR;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rsrc, (__attribute__((address_space(3))) void *)(kl + j * 1024), 16,
+                row * ROWB + ((pos ^ swz<D>(row)) << 4), 0, 0, 0);
+        }
+#endif
+    };
+    copy_keys();
     // query rows of a unit are contiguous in r: [b][l][kvh*g + r / Tq][r % Tq][D]
     const uint16_t *Qg = static_cast<const uint16_t *>(p.q);
     const uint16_t *qrow = Qg + ((((size_t)b * p.L + l) * p.Hq + (size_t)kvh * p.g) * p.Tq + (size_t)(row_ok ? r : 0)) * D;
@@ -114,93 +146,75 @@ __global__ __launch_bounds__(kThreads) void ap_weights_mfma_kernel(APParams p)
         if (row_ok) v = *reinterpret_cast<const uint4 *>(qrow + ks * 16 + half * 8);
         qf[ks] = __builtin_bit_cast(bf16x8, v);
     }
-    const uint16_t *kbase = static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S) * D;
+    __builtin_amdgcn_s_waitcnt(0);   // this wave's copies have landed ...
+    __syncthreads();                 // ... and so have the other waves'
+    if (!blk_ok) return;   // (no barrier follows)
 
-    // staging: piece id = i*256 + tid -> key row id / PPR, 16-byte piece id % PPR
-    uint4 stage[NLD];
-    auto load_chunk = [&](int c) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int id = i * kThreads + tid, row = id / PPR, pc = id % PPR;
-            const int key = c * CHK + row;
-            stage[i] = key < S ? *reinterpret_cast<const uint4 *>(kbase + (size_t)key * D + pc * 8)
-                               : make_uint4(0u, 0u, 0u, 0u);
-        }
-    };
-    auto store_chunk = [&](int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int id = i * kThreads + tid, row = id / PPR, pc = id % PPR;
-            *reinterpret_cast<uint4 *>(&kl[buf][row * ROWB + ((pc ^ swz<D>(row)) << 4)]) = stage[i];
-        }
-    };
-    // logits of the 32 keys of block kb of a chunk against this wave's 32 rows: lane (n, half) gets
-    // row n, keys 8*(v/4) + 4*half + v%4
-    auto logits = [&](int buf, int kb) __attribute__((always_inline)) -> f32x16 {
+    // logits of the 32 keys of block kb against this wave's 32 rows: lane (n, half) gets row n,
+    // keys 8*(v/4) + 4*half + v%4 of the block; keys the row does not see are set to -inf
+    auto logits = [&](int kb) __attribute__((always_inline)) -> f32x16 {
         f32x16 a;
 #pragma unroll
         for (int v = 0; v < 16; ++v) a[v] = 0.f;
         const int row = kb * 32 + n;
-        const unsigned char *rp = &kl[buf][row * ROWB];
+        const unsigned char *rp = &kl[row * ROWB];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(rp + (((2 * ks + half) ^ swz<D>(row)) << 4));
             a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], a, 0, 0, 0);
         }
+        const int key0 = k0 + kb * 32;
+        if (__any(key0 + 32 > row_end)) {   // some row of the wave does not see all 32 keys
+            const int lim = row_end - key0 - 4 * half;
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (8 * (v >> 2) + (v & 3) >= lim) a[v] = -INFINITY;
+        }
         return a;
     };
 
-    const int nchunks = (S + CHK - 1) / CHK;
-    float mx = -INFINITY, M = 0.f, z = 0.f;
-    for (int sweep = 0; sweep < 2; ++sweep) {
-        load_chunk(0);
-        store_chunk(0);
-        __syncthreads();
-        for (int c = 0; c < nchunks; ++c) {
-            const int buf = c & 1;
-            if (c + 1 < nchunks) load_chunk(c + 1);
-            if (blk_ok) {
+    // the logits of all KR keys stay in registers between the maximum and the exponentials
+    constexpr int NKBW = KR / 32;
+    const int nkb = (kn + 31) / 32;
+    f32x16 x[NKBW];
+    float mx = -INFINITY;
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const int key0 = c * CHK + kb * 32;
-                    if (key0 >= S) break;   // (the last chunk may hold one block only: E has no room for another)
-                    f32x16 a = logits(buf, kb);
-                    if (__any(key0 + 32 > row_end)) {   // some row of the wave does not see all 32 keys
-                        const int lim = row_end - key0 - 4 * half;
+    for (int kb = 0; kb < NKBW; ++kb) {
+        if (kb < nkb) {
+            x[kb] = logits(kb);
 #pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            if (8 * (v >> 2) + (v & 3) >= lim) a[v] = -INFINITY;
-                    }
-                    if (sweep == 0) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, a[v]);
-                    } else {
-                        uint32_t pk[8];
-#pragma unroll
-                        for (int v = 0; v < 16; v += 2) {
-                            const float e0 = __builtin_amdgcn_exp2f(fmaf(a[v], p.c, -M));
-                            const float e1 = __builtin_amdgcn_exp2f(fmaf(a[v + 1], p.c, -M));
-                            z += e0 + e1;
-                            pk[v >> 1] = pack_f16(e0, e1);
-                        }
-                        if (row_ok) {
-                            uint4 *dst = reinterpret_cast<uint4 *>(p.E + e_block_offset(p, rbl, l, c * 2 + kb) + n * 64 + half * 32);
-                            dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-                            dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-                        }
-                    }
-                }
-            }
-            if (c + 1 < nchunks) store_chunk(buf ^ 1);
-            __syncthreads();
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, x[kb][v]);
         }
-        if (sweep == 0) {
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            M = row_ok ? mx * p.c : 0.f;   // (c > 0: the largest logit gives the largest exponent)
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // (c > 0: the largest logit gives the largest exponent.)  A row that sees none of this split's
+    // keys (causal reading) gets e = 0 everywhere and the "no key yet" exponent.
+    const float M = mx > -INFINITY ? mx * p.c : 0.f;
+    float z = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < NKBW; ++kb) {
+        if (kb < nkb) {
+            uint32_t pk[8];
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const float e0 = __builtin_amdgcn_exp2f(fmaf(x[kb][v], p.c, -M));
+                const float e1 = __builtin_amdgcn_exp2f(fmaf(x[kb][v + 1], p.c, -M));
+                z += e0 + e1;
+                pk[v >> 1] = pack_f16(e0, e1);
+            }
+            if (row_ok) {
+                uint4 *dst = reinterpret_cast<uint4 *>(p.E + e_block_offset(p, rbl, l, sp * NKBW + kb) + n * 64 + half * 32);
+                dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+            }
         }
     }
     z += __shfl_xor(z, 32, 64);
-    if (row_ok && half == 0) p.rowZ[((size_t)rbl * 32 + n) * p.L + l] = z;
+    if (row_ok && half == 0) {
+        const size_t o = (((size_t)rbl * 32 + n) * p.nsplit + sp) * p.L + l;
+        p.rowM[o] = mx > -INFINITY ? M : kMInit;
+        p.rowZ[o] = z;
+    }
 }
 
 // Portable weights kernel: one wave per (row of the batch, layer); lane = key.
@@ -219,8 +233,8 @@ __global__ __launch_bounds__(64) void ap_weights_generic_kernel(APParams p)
     const int l = blockIdx.x % p.L;
     const int rowl = blockIdx.x / p.L;
     const int rbl = rowl >> 5, n = rowl & 31;
-    const int grb = p.grg0 * 4 + rbl;
-    const int u = grb / (p.NRG * 4), rb = grb % (p.NRG * 4);
+    const int grb = p.grg0 * p.NW + rbl;
+    const int u = grb / (p.NRG * p.NW), rb = grb % (p.NRG * p.NW);
     const int r = rb * 32 + n;
     if (r >= p.Rk) return;
     const int b = u / p.Hkv, kvh = u % p.Hkv;
@@ -252,22 +266,70 @@ __global__ __launch_bounds__(64) void ap_weights_generic_kernel(APParams p)
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
-    if (lane == 0) p.rowZ[((size_t)rbl * 32 + n) * p.L + l] = z;
+    if (lane == 0) {   // (this kernel does not split the keys: nsplit is 1)
+        p.rowM[((size_t)rbl * 32 + n) * p.L + l] = mx;
+        p.rowZ[((size_t)rbl * 32 + n) * p.L + l] = z;
+    }
+}
+
+// Between the two: the key splits' exponents of a (row, layer) are replaced by their factors
+// against the largest, 2^(m_s - max m), and Z is summed at that common exponent.  One workgroup
+// per row of the batch.
+__global__ __launch_bounds__(kThreads) void ap_scale_kernel(APParams p)
+{
+    __shared__ float red[kThreads];
+    const int rowl = blockIdx.x;
+    const int grb = p.grg0 * p.NW + (rowl >> 5);
+    if ((grb % (p.NRG * p.NW)) * 32 + (rowl & 31) >= p.Rk) return;   // no such row
+    // thread = (group gi of key splits, layer l): Lq layers side by side, kThreads / Lq groups
+    const int Lq = p.L <= 32 ? 32 : (p.L <= 64 ? 64 : 128), NG = kThreads / Lq;
+    const int l = threadIdx.x % Lq, gi = threadIdx.x / Lq;
+    const bool ok = l < p.L;
+    float *pm = p.rowM + (size_t)rowl * p.nsplit * p.L + l;
+    const float *pz = p.rowZ + (size_t)rowl * p.nsplit * p.L + l;
+    float mxv = kMInit;
+    if (ok)
+        for (int sp = gi; sp < p.nsplit; sp += NG) mxv = fmaxf(mxv, pm[(size_t)sp * p.L]);
+    red[threadIdx.x] = mxv;
+    __syncthreads();
+    for (int g2 = 0; g2 < NG; ++g2) mxv = fmaxf(mxv, red[g2 * Lq + l]);
+    __syncthreads();
+    float z = 0.f;
+    if (ok)
+        for (int sp = gi; sp < p.nsplit; sp += NG) {
+            const float f = exp2f(pm[(size_t)sp * p.L] - mxv);
+            z += pz[(size_t)sp * p.L] * f;
+            pm[(size_t)sp * p.L] = f;
+        }
+    red[threadIdx.x] = z;
+    __syncthreads();
+    if (ok && gi == 0) {
+        float zt = 0.f;
+        for (int g2 = 0; g2 < NG; ++g2) zt += red[g2 * Lq + l];   // fixed order
+        p.rowZt[(size_t)rowl * p.L + l] = 1.f / zt;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
-// 2. Gram kernel: one workgroup per row of the batch.  NB = 32-layer blocks (L <= 32*NB).
-template <int NB>
-__global__ __launch_bounds__(kThreads) void ap_gram_kernel(APParams p)
+// 2. Gram kernel.  A workgroup of 8 waves takes 8*RPW rows of one 32-row block (wave w the rows
+// w*RPW ..) and the key blocks [y*kb_per, (y+1)*kb_per) of them: all its waves walk the same key
+// blocks at about the same time, so that what it fetches of a (layer, key block) is one contiguous
+// run.  NB = 32-layer blocks (L <= 32*NB).  The sums go to Gpart[row][y] in result-register order
+// (block a, register v, lane): element v of lane (m, kg) of block (bi, bj) is
+// G[bi*32 + 8*(v/4) + 4*kg + v%4][bj*32 + m].
+template <int NB, int RPW>
+__global__ __launch_bounds__(512) void ap_gram_kernel(APParams p, int ksp, int kb_per)
 {
-    extern __shared__ float G[];   // [Lp][Lp], Lp = 32*NB; blocks (bi >= bj) are filled
-    constexpr int Lp = 32 * NB, NACC = NB * (NB + 1) / 2;
-    const int rowl = blockIdx.x, rbl = rowl >> 5, row32 = rowl & 31;
-    const int grb = p.grg0 * 4 + rbl;
-    const int rb = grb % (p.NRG * 4);
-    if (rb * 32 + row32 >= p.Rk) return;   // (the whole workgroup)
+    constexpr int NACC = NB * (NB + 1) / 2, RWG = 8 * RPW;
+    const int sub = blockIdx.x % (32 / RWG), rbl = blockIdx.x / (32 / RWG), y = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, m = lane & 31, kg = lane >> 5;
-    const int L = p.L;
+    const int grb = p.grg0 * p.NW + rbl;
+    const int rb = grb % (p.NRG * p.NW);
+    const int row0 = sub * RWG + w * RPW;           // first row (of the 32-row block) of this wave
+    const int L = p.L, nsplit = p.nsplit;
+    int nrows = p.Rk - (rb * 32 + row0);            // rows of this wave that exist
+    nrows = nrows < 0 ? 0 : (nrows > RPW ? RPW : nrows);
+    if (nrows == 0) return;
 
     const unsigned char *src[NB];
     bool lok[NB];
@@ -275,35 +337,59 @@ __global__ __launch_bounds__(kThreads) void ap_gram_kernel(APParams p)
     for (int lb = 0; lb < NB; ++lb) {
         const int l = lb * 32 + m;
         lok[lb] = l < L;
-        src[lb] = p.E + e_block_offset(p, rbl, lok[lb] ? l : 0, 0) + row32 * 64 + kg * 32;
+        src[lb] = p.E + e_block_offset(p, rbl, lok[lb] ? l : 0, 0) + row0 * 64 + kg * 32;
     }
-    f32x16 acc[NACC];
+    f32x16 acc[RPW][NACC];
 #pragma unroll
-    for (int a = 0; a < NACC; ++a)
+    for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[a][v] = 0.f;
+        for (int a = 0; a < NACC; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[rr][a][v] = 0.f;
 
-    for (int i = tid; i < Lp * Lp; i += kThreads) G[i] = 0.f;
-
-    constexpr int UNR = NB == 1 ? 4 : (NB == 2 ? 2 : 1);
-    const int NKB = p.NKB;
-    for (int kb0 = w; kb0 < NKB; kb0 += 4 * UNR) {
-        uint4 raw[UNR][NB][2];
+    const int bps = p.kps / 32;   // key blocks per key split of the weights kernel
+    const int kb_begin = y * kb_per, kb_end = min(p.NKB, kb_begin + kb_per);
+    int cur_sp = -1;
+    f16x8 fsc[RPW][NB];
+    for (int kb = kb_begin; kb < kb_end; ++kb) {
+        if (nsplit > 1 && kb / bps != cur_sp) {   // a new key split: its factors to the common exponents
+            cur_sp = kb / bps;
 #pragma unroll
-        for (int uu = 0; uu < UNR; ++uu) {
-            const int kb = kb0 + 4 * uu;
+            for (int rr = 0; rr < RPW; ++rr)
+#pragma unroll
+                for (int lb = 0; lb < NB; ++lb) {
+                    float f = 0.f;
+                    if (lok[lb] && rr < nrows)
+                        f = p.rowM[(((size_t)rbl * 32 + row0 + rr) * nsplit + cur_sp) * L + lb * 32 + m];
+                    const _Float16 fh = (_Float16)f;
+                    fsc[rr][lb] = f16x8{fh, fh, fh, fh, fh, fh, fh, fh};
+                }
+        }
+        f16x8 op[RPW][NB][2];
+#pragma unroll
+        for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
             for (int lb = 0; lb < NB; ++lb) {
-                raw[uu][lb][0] = raw[uu][lb][1] = make_uint4(0u, 0u, 0u, 0u);
-                if (lok[lb] && kb < NKB) {
-                    const uint4 *s4 = reinterpret_cast<const uint4 *>(src[lb] + (size_t)kb * 2048);
-                    raw[uu][lb][0] = s4[0];
-                    raw[uu][lb][1] = s4[1];
+                uint4 r0 = make_uint4(0u, 0u, 0u, 0u), r1 = r0;
+                if (lok[lb] && rr < nrows) {
+                    const uint4 *s4 = reinterpret_cast<const uint4 *>(src[lb] + (size_t)kb * 2048 + rr * 64);
+                    r0 = s4[0];
+                    r1 = s4[1];
                 }
+                op[rr][lb][0] = __builtin_bit_cast(f16x8, r0);
+                op[rr][lb][1] = __builtin_bit_cast(f16x8, r1);
             }
+        if (nsplit > 1) {
+#pragma unroll
+            for (int rr = 0; rr < RPW; ++rr)
+#pragma unroll
+                for (int lb = 0; lb < NB; ++lb) {
+                    op[rr][lb][0] = op[rr][lb][0] * fsc[rr][lb];
+                    op[rr][lb][1] = op[rr][lb][1] * fsc[rr][lb];
+                }
         }
 #pragma unroll
-        for (int uu = 0; uu < UNR; ++uu) {
+        for (int rr = 0; rr < RPW; ++rr) {
             int a = 0;
 #pragma unroll
             for (int bi = 0; bi < NB; ++bi)
@@ -311,37 +397,56 @@ __global__ __launch_bounds__(kThreads) void ap_gram_kernel(APParams p)
                 for (int bj = 0; bj <= bi; ++bj, ++a)
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
-                        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                            __builtin_bit_cast(f16x8, raw[uu][bi][j]), __builtin_bit_cast(f16x8, raw[uu][bj][j]),
-                            acc[a], 0, 0, 0);
+                        acc[rr][a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[rr][bi][j], op[rr][bj][j], acc[rr][a], 0, 0, 0);
         }
     }
-    // the four waves' sums, added in wave order: result element v of lane (m, kg) is
-    // G[bi*32 + 8*(v/4) + 4*kg + v%4][bj*32 + m]
-    for (int round = 0; round < 4; ++round) {
-        __syncthreads();
-        if (w == round) {
-            int a = 0;
 #pragma unroll
-            for (int bi = 0; bi < NB; ++bi)
+    for (int rr = 0; rr < RPW; ++rr) {
+        if (rr >= nrows) break;
+        float *dst = p.Gpart + (((size_t)rbl * 32 + row0 + rr) * ksp + y) * (NACC * 1024) + lane;
 #pragma unroll
-                for (int bj = 0; bj <= bi; ++bj, ++a)
+        for (int a = 0; a < NACC; ++a)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        G[(bi * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)) * Lp + bj * 32 + m] += acc[a][v];
-        }
+            for (int v = 0; v < 16; ++v) dst[a * 1024 + v * 64] = acc[rr][a][v];
     }
+}
+
+// One workgroup per row of the batch: the row's partial Gram matrices are added in order, the key
+// splits' Z are brought to the common exponents, and cos_ij, dist_ij are written for i > j.
+__global__ __launch_bounds__(kThreads) void ap_row_final_kernel(APParams p, int ksp)
+{
+    extern __shared__ float sm_rf[];
+    const int L = p.L, NB = (L + 31) / 32, NACC = NB * (NB + 1) / 2;
+    float *Gs = sm_rf;                 // [NACC*1024]
+    float *Zs = Gs + NACC * 1024;      // [L]: 1 / Z of the layer
+    const int rowl = blockIdx.x, rbl = rowl >> 5, row32 = rowl & 31;
+    const int grb = p.grg0 * p.NW + rbl;
+    const int rb = grb % (p.NRG * p.NW);
+    if (rb * 32 + row32 >= p.Rk) return;
+    const int tid = threadIdx.x;
+    const float *gp = p.Gpart + (size_t)rowl * ksp * (NACC * 1024);
+    for (int i = tid; i < NACC * 1024; i += kThreads) {
+        float g = 0.f;
+        for (int y = 0; y < ksp; ++y) g += gp[(size_t)y * (NACC * 1024) + i];
+        Gs[i] = g;
+    }
+    for (int l = tid; l < L; l += kThreads) Zs[l] = p.rowZt[(size_t)rowl * L + l];
     __syncthreads();
-    const float *Z = p.rowZ + (size_t)rowl * L;
+    auto G = [&](int i, int j) -> float {   // i >= j
+        const int bi = i >> 5, bj = j >> 5, ii = i & 31;
+        const int a = bi * (bi + 1) / 2 + bj;
+        const int v = ((ii >> 3) << 2) | (ii & 3), kg = (ii >> 2) & 1;
+        return Gs[a * 1024 + v * 64 + kg * 32 + (j & 31)];
+    };
     float *oc = p.row_cos + (size_t)rowl * L * L;
     float *od = p.row_dist + (size_t)rowl * L * L;
     for (int e = tid; e < L * L; e += kThreads) {
         const int i = e / L, j = e % L;
         if (i <= j) continue;
-        const float gij = G[i * Lp + j], gii = G[i * Lp + i], gjj = G[j * Lp + j];
+        const float gij = G(i, j), gii = G(i, i), gjj = G(j, j);
         oc[e] = gij * rsqrtf(gii * gjj);
         if (p.want_dist) {
-            const float zi = 1.f / Z[i], zj = 1.f / Z[j];
+            const float zi = Zs[i], zj = Zs[j];
             od[e] = sqrtf(fmaxf(gii * zi * zi + gjj * zj * zj - 2.f * gij * zi * zj, 0.f));
         }
     }
@@ -357,8 +462,9 @@ __global__ __launch_bounds__(kThreads) void ap_reduce_kernel(APParams p, int u0)
     // rows of unit u that this batch holds, and those of them that belong to head hg
     const int rg_lo = max(p.grg0, u * p.NRG) - u * p.NRG;
     const int rg_hi = min(p.grg0 + p.nrg, (u + 1) * p.NRG) - u * p.NRG;
-    const int r_lo = max(rg_lo * kRowsPerGroup, hg * p.Tq);
-    const int r_hi = min(min(rg_hi * kRowsPerGroup, p.Rk), (hg + 1) * p.Tq);
+    const int rpg = p.NW * 32;   // rows per row group
+    const int r_lo = max(rg_lo * rpg, hg * p.Tq);
+    const int r_hi = min(min(rg_hi * rpg, p.Rk), (hg + 1) * p.Tq);
     if (e >= LL || r_lo >= r_hi) return;
     const int i = e / p.L, j = e % p.L;
     if (i <= j) return;
@@ -368,7 +474,7 @@ __global__ __launch_bounds__(kThreads) void ap_reduce_kernel(APParams p, int u0)
     // the batches are cut
     float cs = p.head_cos[o], ds = p.want_dist ? p.head_dist[o] : 0.f;
     for (int r = r_lo; r < r_hi; ++r) {
-        const size_t rowl = (size_t)(u * p.NRG + r / kRowsPerGroup - p.grg0) * kRowsPerGroup + r % kRowsPerGroup;
+        const size_t rowl = (size_t)(u * p.NRG + r / rpg - p.grg0) * rpg + r % rpg;
         cs += p.row_cos[rowl * LL + e];
         if (p.want_dist) ds += p.row_dist[rowl * LL + e];
     }
@@ -482,24 +588,38 @@ __global__ __launch_bounds__(kSelThreads) void select_all_kernel(
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct APPlan {
-    int NRG, NKB, total_rg, nrg_batch;
-    size_t head_cos_off, head_dist_off, rowz_off, row_cos_off, row_dist_off, e_off, total_bytes;
+    int NW, NRG, NKB, nsplit, kps, total_rg, nrg_batch, ksp, kb_per;
+    size_t head_cos_off, head_dist_off, rowm_off, rowz_off, rowzt_off, gpart_off, row_cos_off, row_dist_off, e_off, total_bytes;
     bool mfma;
 };
 
-// Sizes for a batch of nrg row groups.
+constexpr int kGramTargetWorkgroups = 1024;
+
+// Sizes for a batch of nrg row groups (NW, NRG, NKB, nsplit must be set).
 void ap_layout(const krul_shape_t *s, int nrg, APPlan *pl)
 {
-    const size_t L = s->n_layers, LL = L * L;
+    const size_t L = s->n_layers, LL = L * L, NB = (L + 31) / 32, NACC = NB * (NB + 1) / 2;
     const size_t heads = (size_t)s->batch * s->n_q_heads * LL * sizeof(float);
-    const size_t rows = (size_t)nrg * kRowsPerGroup;
+    const size_t rows = (size_t)nrg * pl->NW * 32;
+    // the Gram kernel splits the keys until it has enough workgroups, but keeps at least 8 key blocks
+    // per workgroup so that the partial matrices stay small beside the weights
+    const long long row_wgs = (long long)nrg * pl->NW * (NB == 1 ? 1 : (NB == 2 ? 2 : 4));
+    long long ksp = (kGramTargetWorkgroups + row_wgs - 1) / row_wgs;
+    const long long ksp_max = pl->NKB / 8 > 1 ? pl->NKB / 8 : 1;
+    if (ksp > ksp_max) ksp = ksp_max;
+    if (ksp > 64) ksp = 64;
+    pl->kb_per = (int)((pl->NKB + ksp - 1) / ksp);
+    pl->ksp = (pl->NKB + pl->kb_per - 1) / pl->kb_per;
     size_t off = 0;
     pl->head_cos_off = off; off += align_up(heads);
     pl->head_dist_off = off; off += align_up(heads);
-    pl->rowz_off = off; off += align_up(rows * L * sizeof(float));
+    pl->rowm_off = off; off += align_up(rows * L * pl->nsplit * sizeof(float));
+    pl->rowz_off = off; off += align_up(rows * L * pl->nsplit * sizeof(float));
+    pl->rowzt_off = off; off += align_up(rows * L * sizeof(float));
+    pl->gpart_off = off; off += align_up(rows * pl->ksp * NACC * 1024 * sizeof(float));
     pl->row_cos_off = off; off += align_up(rows * LL * sizeof(float));
     pl->row_dist_off = off; off += align_up(rows * LL * sizeof(float));
-    pl->e_off = off; off += align_up((size_t)nrg * 4 * L * pl->NKB * 2048);
+    pl->e_off = off; off += align_up((size_t)nrg * pl->NW * L * (pl->NKB | 1) * 2048);
     pl->total_bytes = off;
     pl->nrg_batch = nrg;
 }
@@ -516,24 +636,46 @@ int ap_plan(const krul_shape_t *s, size_t max_bytes, APPlan *pl)
     if (s->n_layers > kMaxLayersAllPairs) return KRUL_EUNSUPPORTED;
     const long long g = s->n_q_heads / s->n_kv_heads, Rk = g * s->n_query;
     if (Rk > INT32_MAX || (long long)s->batch * s->n_q_heads * s->n_query > INT32_MAX) return KRUL_EUNSUPPORTED;
-    pl->NRG = (int)((Rk + kRowsPerGroup - 1) / kRowsPerGroup);
+    if (s->n_hist * (long long)s->head_dim * 4 >= (1ll << 31)) return KRUL_EUNSUPPORTED;
+    const long long NRB = (Rk + 31) / 32;   // 32-row blocks per unit
+    pl->NW = NRB >= 3 ? 4 : (int)NRB;
+    pl->NRG = (int)((NRB + pl->NW - 1) / pl->NW);
     pl->NKB = (s->n_hist + 31) / 32;
     const long long total = (long long)s->batch * s->n_kv_heads * pl->NRG;
-    if (total * kRowsPerGroup > INT32_MAX / 4) return KRUL_EUNSUPPORTED;
+    if (total * pl->NW * 32 > INT32_MAX / 4) return KRUL_EUNSUPPORTED;
     pl->total_rg = (int)total;
     pl->mfma = s->dtype == KRUL_BF16 && (s->head_dim == 64 || s->head_dim == 128) &&
                !(s->flags & KRUL_FLAG_GENERIC_KERNEL);
-    if (s->n_hist * (long long)s->head_dim * 4 >= (1ll << 31)) return KRUL_EUNSUPPORTED;
+    // key splits of the weights kernel: one per kKeysPerSplit keys (the portable kernel does not split)
+    if (pl->mfma) {
+        pl->kps = kKeysPerSplit;
+        pl->nsplit = (s->n_hist + kKeysPerSplit - 1) / kKeysPerSplit;
+    } else {
+        pl->nsplit = 1;
+        pl->kps = pl->NKB * 32;
+    }
+
     const size_t budget = max_bytes ? max_bytes : kDefaultBudget;
     ap_layout(s, 1, pl);
-    const size_t fixed = pl->rowz_off;   // the head sums do not grow with the batch
+    const size_t fixed = pl->rowm_off;   // the head sums do not grow with the batch
     const size_t per_group = pl->total_bytes - fixed;
     long long nrg = budget > fixed ? (long long)((budget - fixed) / per_group) : 0;
     if (nrg < 1) nrg = 1;
     if (nrg > total) nrg = total;
     ap_layout(s, (int)nrg, pl);
-    while (pl->total_bytes > budget && nrg > 1) ap_layout(s, (int)--nrg, pl);   // (alignment padding)
+    while (pl->total_bytes > budget && nrg > 1) ap_layout(s, (int)--nrg, pl);   // (padding, partial matrices)
     return KRUL_OK;
+}
+
+template <int D>
+void launch_weights(const APParams &p, hipStream_t st)
+{
+    const dim3 grid(p.nrg * p.L * p.nsplit);
+    switch (p.NW) {
+    case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1>), grid, dim3(64), 0, st, p); break;
+    case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2>), grid, dim3(128), 0, st, p); break;
+    default: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4>), grid, dim3(256), 0, st, p); break;
+    }
 }
 
 }  // namespace
@@ -549,21 +691,17 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
                   float *head_score, void *workspace, size_t workspace_bytes, hipStream_t st)
 {
     APPlan pl;
-    int rc = ap_plan(s, 0, &pl);
+    int rc = ap_plan(s, 1, &pl);   // the smallest batch: one row group
     if (rc != KRUL_OK) return rc;
     if (!q || !k || !pair_score) return KRUL_EINVAL;
     if (((uintptr_t)q | (uintptr_t)k) & 15) return KRUL_EINVAL;
     if (((uintptr_t)pair_score | (uintptr_t)pair_dist | (uintptr_t)head_score) & 3) return KRUL_EINVAL;
-    if (!workspace || ((uintptr_t)workspace & 255)) return KRUL_EWORKSPACE;
-    // the batch is what the caller's workspace holds: the smallest (one row group) must fit
-    {
-        APPlan one = pl;
-        ap_layout(s, 1, &one);
-        if (workspace_bytes < one.total_bytes) return KRUL_EWORKSPACE;
-        rc = ap_plan(s, workspace_bytes, &pl);
-        if (rc != KRUL_OK) return rc;
-        if (pl.total_bytes > workspace_bytes) return KRUL_EWORKSPACE;
-    }
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pl.total_bytes) return KRUL_EWORKSPACE;
+    // the batch is what the caller's workspace holds
+    rc = ap_plan(s, workspace_bytes, &pl);
+    if (rc != KRUL_OK) return rc;
+    if (pl.total_bytes > workspace_bytes) return KRUL_EWORKSPACE;
+
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     APParams p;
     p.q = q;
@@ -580,11 +718,18 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
     p.causal = (s->flags & KRUL_FLAG_CAUSAL) != 0;
     const float scale = s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->head_dim);
     p.c = scale * 1.4426950408889634f;
+    p.NW = pl.NW;
     p.NRG = pl.NRG;
     p.NKB = pl.NKB;
+    p.NKBs = pl.NKB | 1;
+    p.nsplit = pl.nsplit;
+    p.kps = pl.kps;
     p.want_dist = pair_dist != nullptr;
     p.E = ws + pl.e_off;
+    p.rowM = reinterpret_cast<float *>(ws + pl.rowm_off);
     p.rowZ = reinterpret_cast<float *>(ws + pl.rowz_off);
+    p.rowZt = reinterpret_cast<float *>(ws + pl.rowzt_off);
+    p.Gpart = reinterpret_cast<float *>(ws + pl.gpart_off);
     p.row_cos = reinterpret_cast<float *>(ws + pl.row_cos_off);
     p.row_dist = reinterpret_cast<float *>(ws + pl.row_dist_off);
     p.head_cos = reinterpret_cast<float *>(ws + pl.head_cos_off);
@@ -597,28 +742,30 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
         hipLaunchKernelGGL(ap_fill_kernel, dim3((unsigned)((n_head + 255) / 256)), dim3(256), 0, st, p.head_dist, n_head, 0.f);
     if (hipGetLastError() != hipSuccess) return KRUL_ELAUNCH;
 
-    const int NB = (L + 31) / 32;
-    const size_t gram_smem = (size_t)(32 * NB) * (32 * NB) * sizeof(float);
+    const int NB = (L + 31) / 32, NACC = NB * (NB + 1) / 2;
+    const size_t rf_smem = ((size_t)NACC * 1024 + L) * sizeof(float);
     for (int g0 = 0; g0 < pl.total_rg; g0 += pl.nrg_batch) {
         p.grg0 = g0;
         p.nrg = pl.nrg_batch < pl.total_rg - g0 ? pl.nrg_batch : pl.total_rg - g0;
-        const int rows = p.nrg * kRowsPerGroup;
+        const int rblocks = p.nrg * p.NW, rows = rblocks * 32;
         if (pl.mfma) {
             if (p.d == 128)
-                hipLaunchKernelGGL(ap_weights_mfma_kernel<128>, dim3(p.nrg * L), dim3(kThreads), 0, st, p);
+                launch_weights<128>(p, st);
             else
-                hipLaunchKernelGGL(ap_weights_mfma_kernel<64>, dim3(p.nrg * L), dim3(kThreads), 0, st, p);
+                launch_weights<64>(p, st);
         } else if (s->dtype == KRUL_F32) {
             hipLaunchKernelGGL(ap_weights_generic_kernel<float>, dim3(rows * L), dim3(64), p.d * sizeof(float), st, p);
         } else {
             hipLaunchKernelGGL(ap_weights_generic_kernel<uint16_t>, dim3(rows * L), dim3(64), p.d * sizeof(float), st, p);
         }
+        hipLaunchKernelGGL(ap_scale_kernel, dim3(rows), dim3(kThreads), 0, st, p);
         switch (NB) {
-        case 1: hipLaunchKernelGGL(ap_gram_kernel<1>, dim3(rows), dim3(kThreads), gram_smem, st, p); break;
-        case 2: hipLaunchKernelGGL(ap_gram_kernel<2>, dim3(rows), dim3(kThreads), gram_smem, st, p); break;
-        case 3: hipLaunchKernelGGL(ap_gram_kernel<3>, dim3(rows), dim3(kThreads), gram_smem, st, p); break;
-        default: hipLaunchKernelGGL(ap_gram_kernel<4>, dim3(rows), dim3(kThreads), gram_smem, st, p); break;
+        case 1: hipLaunchKernelGGL((ap_gram_kernel<1, 4>), dim3(rblocks, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
+        case 2: hipLaunchKernelGGL((ap_gram_kernel<2, 2>), dim3(rblocks * 2, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
+        case 3: hipLaunchKernelGGL((ap_gram_kernel<3, 1>), dim3(rblocks * 4, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
+        default: hipLaunchKernelGGL((ap_gram_kernel<4, 1>), dim3(rblocks * 4, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
         }
+        hipLaunchKernelGGL(ap_row_final_kernel, dim3(rows), dim3(kThreads), rf_smem, st, p, pl.ksp);
         const int u0 = g0 / p.NRG, u1 = (g0 + p.nrg - 1) / p.NRG;
         hipLaunchKernelGGL(ap_reduce_kernel, dim3((u1 - u0 + 1) * p.g, (LL + kThreads - 1) / kThreads), dim3(kThreads),
                            0, st, p, u0);
