@@ -221,7 +221,7 @@ int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
  *   workspace       device, 256-byte aligned.  The attention weights of a batch of query rows are kept
  *                   in it (fp16), as the paper keeps them (Sec. 5), so its size sets how many rows one
  *                   batch holds: krul_all_pairs_workspace(shape, max_bytes) returns the bytes for the
- *                   largest batch that fits max_bytes (max_bytes 0: a default budget of 2 GiB; never
+ *                   largest batch that fits max_bytes (max_bytes 0: a default budget of 4 GiB; never
  *                   less than the bytes for the smallest batch, 128 rows of one kv head), or 0 if the
  *                   shape is not supported.  Any size from the smallest batch's up is accepted by the
  *                   call; more memory means fewer, larger launches.

@@ -43,7 +43,7 @@ typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kThreads = 256;
-constexpr int kKeysPerSplit = 256;   // keys of one weights-kernel workgroup (held in LDS)
+constexpr int kKeysPerSplit = 128;   // keys of one step of a weights-kernel workgroup (an LDS buffer)
 
 struct APParams {
     const void *q;
@@ -54,12 +54,11 @@ struct APParams {
     int NW;             // 32-row blocks per row group = waves of a weights-kernel workgroup (1, 2 or 4)
     int NRG;            // row groups per unit
     int NKB;            // 32-key blocks per row
-    int NKBs;           // ... and the stride between layers in E, in blocks: odd, so that the layers' streams
-                        // of one key block do not all fall on the same memory channel
     int nsplit, kps;    // key splits of the weights kernel, keys per split (a multiple of 32)
+    int tpw;            // key splits that one weights-kernel workgroup walks
     int grg0, nrg;      // this batch: global row groups [grg0, grg0 + nrg)
     int want_dist;
-    unsigned char *E;   // [nrg*NW][L][NKBs][32][64 bytes]; e = 2^(x - m) with m of the row, layer and key split
+    unsigned char *E;   // [nrg*NW][NKB][L][32][64 bytes]; e = 2^(x - m) with m of the row, layer and key split
     float *rowM;        // [nrg*NW*32][nsplit][L]  reference exponent m; then the factor 2^(m - largest m of the row, layer)
     float *rowZ;        // [nrg*NW*32][nsplit][L]  sum of e over the split's keys
     float *rowZt;       // [nrg*NW*32][L]          1 / (sum of e over all keys, at the common exponent)
@@ -72,7 +71,7 @@ struct APParams {
 
 __device__ inline size_t e_block_offset(const APParams &p, int rbl, int l, int kb)
 {
-    return ((((size_t)rbl * p.L + l) * p.NKBs + kb) * 32) * 64;
+    return ((((size_t)rbl * p.NKB + kb) * p.L + l) * 32) * 64;
 }
 
 // Row-dependent XOR applied to the 16-byte piece index inside an LDS tile of key rows, so that the
@@ -92,15 +91,17 @@ __device__ inline uint32_t pack_f16(float a, float b)
 // ------------------------------------------------------------------------------------------------
 // 1. weights kernel (bf16, head_dim 64 or 128)
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64) void ap_weights_mfma_kernel(APParams p)
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kernel(APParams p)
 {
-    constexpr int KS = D / 16, PPR = D / 8, ROWB = D * 2, KR = kKeysPerSplit;
-    __shared__ __attribute__((aligned(16))) unsigned char kl[KR * ROWB];
+    constexpr int KS = D / 16, PPR = D / 8, ROWB = D * 2, KR = kKeysPerSplit, NKBW = KR / 32;
+    constexpr int NT = NW * 64, NLD = KR * PPR / NT;
+    __shared__ __attribute__((aligned(16))) unsigned char kl[2][KR * ROWB];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, n = lane & 31;
-    const int sp = blockIdx.x % p.nsplit;
-    const int l = (blockIdx.x / p.nsplit) % p.L;
-    const int rgl = blockIdx.x / (p.nsplit * p.L);
+    const int nkc = (p.nsplit + p.tpw - 1) / p.tpw;   // workgroups along the keys
+    const int kc = blockIdx.x % nkc;
+    const int l = (blockIdx.x / nkc) % p.L;
+    const int rgl = blockIdx.x / (nkc * p.L);
     const int grg = p.grg0 + rgl;
     const int u = grg / p.NRG, rg = grg % p.NRG;
     const int b = u / p.Hkv, kvh = u % p.Hkv;
@@ -111,31 +112,30 @@ __global__ __launch_bounds__(NW * 64) void ap_weights_mfma_kernel(APParams p)
     const int S = p.S;
     const int row_end = row_ok ? (p.causal ? S - p.Tq + r % p.Tq + 1 : S) : 0;   // keys [0, row_end) are seen
 
-    // This workgroup's keys [k0, k0 + kn) are copied HBM -> LDS once, by buffer_load ... lds (no
-    // register staging): wave-instruction j fills the 1 KB at j*1024 (RPI key rows), lane by lane,
-    // so each lane fetches the 16-byte piece that belongs at its LDS position (the XOR swizzle is
-    // applied on the global side); rows past kn are out of the descriptor's range and read as zero.
-    constexpr int RPI = 64 / PPR, NI = KR / RPI / NW;
-    const int k0 = sp * KR, kn = min(KR, S - k0);
-    const uint16_t *kbase = static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S + k0) * D;
-    auto copy_keys = [&]() __attribute__((always_inline)) {
-#if defined(__HIP_DEVICE_COMPILE__)   // (the host pass only needs the kernel's launch stub)
-        const uintptr_t ka = (uintptr_t)kbase;   // wave-uniform: keep the descriptor in scalar registers
-        const uint16_t *kb_u = (const uint16_t *)(((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(ka >> 32)) << 32) |
-                                                  (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)ka));
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint16_t *>(kb_u), 0, __builtin_amdgcn_readfirstlane(kn * ROWB), 0x00020000);
+    // This workgroup walks the key splits [t0, t1) of its rows and layer, KR keys each.  The keys of
+    // split t+1 are fetched into registers while split t is worked on, and written to the other LDS
+    // buffer afterwards.  piece id = i*NT + tid -> key row id / PPR, 16-byte piece id % PPR.
+    const int t0 = kc * p.tpw, t1 = min(p.nsplit, t0 + p.tpw);
+    const uint16_t *klayer = static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S) * D;
+    uint4 stage[NLD];
+    auto fetch = [&](int t) __attribute__((always_inline)) {
+        const int kn = min(KR, S - t * KR);
+        const uint16_t *kbase = klayer + (size_t)t * KR * D;
 #pragma unroll
-        for (int jj = 0; jj < NI; ++jj) {
-            const int j = w * NI + jj;
-            const int row = j * RPI + lane / PPR, pos = lane % PPR;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rsrc, (__attribute__((address_space(3))) void *)(kl + j * 1024), 16,
-                row * ROWB + ((pos ^ swz<D>(row)) << 4), 0, 0, 0);
+        for (int i = 0; i < NLD; ++i) {
+            const int id = i * NT + tid, row = id / PPR, pc = id % PPR;
+            stage[i] = row < kn ? *reinterpret_cast<const uint4 *>(kbase + (size_t)row * D + pc * 8)
+                                : make_uint4(0u, 0u, 0u, 0u);
         }
-#endif
     };
-    copy_keys();
+    auto put = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int id = i * NT + tid, row = id / PPR, pc = id % PPR;
+            *reinterpret_cast<uint4 *>(&kl[buf][row * ROWB + ((pc ^ swz<D>(row)) << 4)]) = stage[i];
+        }
+    };
+    fetch(t0);
     // query rows of a unit are contiguous in r: [b][l][kvh*g + r / Tq][r % Tq][D]
     const uint16_t *Qg = static_cast<const uint16_t *>(p.q);
     const uint16_t *qrow = Qg + ((((size_t)b * p.L + l) * p.Hq + (size_t)kvh * p.g) * p.Tq + (size_t)(row_ok ? r : 0)) * D;
@@ -146,76 +146,78 @@ __global__ __launch_bounds__(NW * 64) void ap_weights_mfma_kernel(APParams p)
         if (row_ok) v = *reinterpret_cast<const uint4 *>(qrow + ks * 16 + half * 8);
         qf[ks] = __builtin_bit_cast(bf16x8, v);
     }
-    __builtin_amdgcn_s_waitcnt(0);   // this wave's copies have landed ...
-    __syncthreads();                 // ... and so have the other waves'
-    if (!blk_ok) return;   // (no barrier follows)
 
-    // logits of the 32 keys of block kb against this wave's 32 rows: lane (n, half) gets row n,
-    // keys 8*(v/4) + 4*half + v%4 of the block; keys the row does not see are set to -inf
-    auto logits = [&](int kb) __attribute__((always_inline)) -> f32x16 {
-        f32x16 a;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) a[v] = 0.f;
-        const int row = kb * 32 + n;
-        const unsigned char *rp = &kl[row * ROWB];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(rp + (((2 * ks + half) ^ swz<D>(row)) << 4));
-            a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], a, 0, 0, 0);
-        }
-        const int key0 = k0 + kb * 32;
-        if (__any(key0 + 32 > row_end)) {   // some row of the wave does not see all 32 keys
-            const int lim = row_end - key0 - 4 * half;
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-                if (8 * (v >> 2) + (v & 3) >= lim) a[v] = -INFINITY;
-        }
-        return a;
-    };
+    for (int t = t0; t < t1; ++t) {
+        const int buf = (t - t0) & 1;
+        put(buf);
+        // the keys of split t are in LDS; every wave has finished reading the other buffer (split t-1)
+        __syncthreads();
+        if (t + 1 < t1) fetch(t + 1);
+        if (!blk_ok) continue;
 
-    // the logits of all KR keys stay in registers between the maximum and the exponentials
-    constexpr int NKBW = KR / 32;
-    const int nkb = (kn + 31) / 32;
-    f32x16 x[NKBW];
-    float mx = -INFINITY;
+        const int k0 = t * KR, kn = min(KR, S - k0), nkb = (kn + 31) / 32;
+        // logits of the 32 keys of block kb against this wave's 32 rows: lane (n, half) gets row n,
+        // keys 8*(v/4) + 4*half + v%4 of the block; keys the row does not see are set to -inf.  The
+        // logits of all KR keys stay in registers between the maximum and the exponentials.
+        f32x16 x[NKBW];
+        float mx = -INFINITY;
 #pragma unroll
-    for (int kb = 0; kb < NKBW; ++kb) {
-        if (kb < nkb) {
-            x[kb] = logits(kb);
+        for (int kb = 0; kb < NKBW; ++kb) {
+            if (kb < nkb) {
+                f32x16 a;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, x[kb][v]);
-        }
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    // (c > 0: the largest logit gives the largest exponent.)  A row that sees none of this split's
-    // keys (causal reading) gets e = 0 everywhere and the "no key yet" exponent.
-    const float M = mx > -INFINITY ? mx * p.c : 0.f;
-    float z = 0.f;
+                for (int v = 0; v < 16; ++v) a[v] = 0.f;
+                const int row = kb * 32 + n;
+                const unsigned char *rp = &kl[buf][row * ROWB];
 #pragma unroll
-    for (int kb = 0; kb < NKBW; ++kb) {
-        if (kb < nkb) {
-            uint32_t pk[8];
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(rp + (((2 * ks + half) ^ swz<D>(row)) << 4));
+                    a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], a, 0, 0, 0);
+                }
+                const int key0 = k0 + kb * 32;
+                if (__any(key0 + 32 > row_end)) {   // some row of the wave does not see all 32 keys
+                    const int lim = row_end - key0 - 4 * half;
 #pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                const float e0 = __builtin_amdgcn_exp2f(fmaf(x[kb][v], p.c, -M));
-                const float e1 = __builtin_amdgcn_exp2f(fmaf(x[kb][v + 1], p.c, -M));
-                z += e0 + e1;
-                pk[v >> 1] = pack_f16(e0, e1);
-            }
-            if (row_ok) {
-                uint4 *dst = reinterpret_cast<uint4 *>(p.E + e_block_offset(p, rbl, l, sp * NKBW + kb) + n * 64 + half * 32);
-                dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-                dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+                    for (int v = 0; v < 16; ++v)
+                        if (8 * (v >> 2) + (v & 3) >= lim) a[v] = -INFINITY;
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, a[v]);
+                x[kb] = a;
             }
         }
-    }
-    z += __shfl_xor(z, 32, 64);
-    if (row_ok && half == 0) {
-        const size_t o = (((size_t)rbl * 32 + n) * p.nsplit + sp) * p.L + l;
-        p.rowM[o] = mx > -INFINITY ? M : kMInit;
-        p.rowZ[o] = z;
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // (c > 0: the largest logit gives the largest exponent.)  A row that sees none of this split's
+        // keys (causal reading) gets e = 0 everywhere and the "no key yet" exponent.
+        const float M = mx > -INFINITY ? mx * p.c : 0.f;
+        float z = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < NKBW; ++kb) {
+            if (kb < nkb) {
+                uint32_t pk[8];
+#pragma unroll
+                for (int v = 0; v < 16; v += 2) {
+                    const float e0 = __builtin_amdgcn_exp2f(fmaf(x[kb][v], p.c, -M));
+                    const float e1 = __builtin_amdgcn_exp2f(fmaf(x[kb][v + 1], p.c, -M));
+                    z += e0 + e1;
+                    pk[v >> 1] = pack_f16(e0, e1);
+                }
+                if (row_ok) {
+                    uint4 *dst = reinterpret_cast<uint4 *>(p.E + e_block_offset(p, rbl, l, t * NKBW + kb) + n * 64 + half * 32);
+                    dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                    dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+                }
+            }
+        }
+        z += __shfl_xor(z, 32, 64);
+        if (row_ok && half == 0) {
+            const size_t o = (((size_t)rbl * 32 + n) * p.nsplit + t) * p.L + l;
+            p.rowM[o] = mx > -INFINITY ? M : kMInit;
+            p.rowZ[o] = z;
+        }
     }
 }
+
 
 // Portable weights kernel: one wave per (row of the batch, layer); lane = key.
 template <typename T>
@@ -311,16 +313,16 @@ __global__ __launch_bounds__(kThreads) void ap_scale_kernel(APParams p)
 }
 
 // ------------------------------------------------------------------------------------------------
-// 2. Gram kernel.  A workgroup of 8 waves takes 8*RPW rows of one 32-row block (wave w the rows
+// 2. Gram kernel.  A workgroup of WV waves takes WV*RPW rows of one 32-row block (wave w the rows
 // w*RPW ..) and the key blocks [y*kb_per, (y+1)*kb_per) of them: all its waves walk the same key
 // blocks at about the same time, so that what it fetches of a (layer, key block) is one contiguous
 // run.  NB = 32-layer blocks (L <= 32*NB).  The sums go to Gpart[row][y] in result-register order
 // (block a, register v, lane): element v of lane (m, kg) of block (bi, bj) is
 // G[bi*32 + 8*(v/4) + 4*kg + v%4][bj*32 + m].
-template <int NB, int RPW>
-__global__ __launch_bounds__(512) void ap_gram_kernel(APParams p, int ksp, int kb_per)
+template <int NB, int RPW, int WV>
+__global__ __launch_bounds__(WV * 64) void ap_gram_kernel(APParams p, int ksp, int kb_per)
 {
-    constexpr int NACC = NB * (NB + 1) / 2, RWG = 8 * RPW;
+    constexpr int NACC = NB * (NB + 1) / 2, RWG = WV * RPW;
     const int sub = blockIdx.x % (32 / RWG), rbl = blockIdx.x / (32 / RWG), y = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, m = lane & 31, kg = lane >> 5;
     const int grb = p.grg0 * p.NW + rbl;
@@ -351,7 +353,22 @@ __global__ __launch_bounds__(512) void ap_gram_kernel(APParams p, int ksp, int k
     const int kb_begin = y * kb_per, kb_end = min(p.NKB, kb_begin + kb_per);
     int cur_sp = -1;
     f16x8 fsc[RPW][NB];
-    for (int kb = kb_begin; kb < kb_end; ++kb) {
+    // the operands of key block kb+1 are fetched while those of kb are multiplied
+    uint4 raw[2][RPW][NB][2];
+    auto fetch = [&](int kb, uint4 (&dst)[RPW][NB][2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int rr = 0; rr < RPW; ++rr)
+#pragma unroll
+            for (int lb = 0; lb < NB; ++lb) {
+                dst[rr][lb][0] = dst[rr][lb][1] = make_uint4(0u, 0u, 0u, 0u);
+                if (lok[lb] && rr < nrows) {
+                    const uint4 *s4 = reinterpret_cast<const uint4 *>(src[lb] + (size_t)kb * L * 2048 + rr * 64);
+                    dst[rr][lb][0] = s4[0];
+                    dst[rr][lb][1] = s4[1];
+                }
+            }
+    };
+    auto multiply = [&](int kb, const uint4 (&cur)[RPW][NB][2]) __attribute__((always_inline)) {
         if (nsplit > 1 && kb / bps != cur_sp) {   // a new key split: its factors to the common exponents
             cur_sp = kb / bps;
 #pragma unroll
@@ -369,25 +386,12 @@ __global__ __launch_bounds__(512) void ap_gram_kernel(APParams p, int ksp, int k
 #pragma unroll
         for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
-            for (int lb = 0; lb < NB; ++lb) {
-                uint4 r0 = make_uint4(0u, 0u, 0u, 0u), r1 = r0;
-                if (lok[lb] && rr < nrows) {
-                    const uint4 *s4 = reinterpret_cast<const uint4 *>(src[lb] + (size_t)kb * 2048 + rr * 64);
-                    r0 = s4[0];
-                    r1 = s4[1];
-                }
-                op[rr][lb][0] = __builtin_bit_cast(f16x8, r0);
-                op[rr][lb][1] = __builtin_bit_cast(f16x8, r1);
-            }
-        if (nsplit > 1) {
+            for (int lb = 0; lb < NB; ++lb)
 #pragma unroll
-            for (int rr = 0; rr < RPW; ++rr)
-#pragma unroll
-                for (int lb = 0; lb < NB; ++lb) {
-                    op[rr][lb][0] = op[rr][lb][0] * fsc[rr][lb];
-                    op[rr][lb][1] = op[rr][lb][1] * fsc[rr][lb];
+                for (int j = 0; j < 2; ++j) {
+                    op[rr][lb][j] = __builtin_bit_cast(f16x8, cur[rr][lb][j]);
+                    if (nsplit > 1) op[rr][lb][j] = op[rr][lb][j] * fsc[rr][lb];
                 }
-        }
 #pragma unroll
         for (int rr = 0; rr < RPW; ++rr) {
             int a = 0;
@@ -398,6 +402,15 @@ __global__ __launch_bounds__(512) void ap_gram_kernel(APParams p, int ksp, int k
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
                         acc[rr][a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[rr][bi][j], op[rr][bj][j], acc[rr][a], 0, 0, 0);
+        }
+    };
+    if (kb_begin < kb_end) fetch(kb_begin, raw[0]);
+    for (int kb = kb_begin; kb < kb_end; kb += 2) {
+        if (kb + 1 < kb_end) fetch(kb + 1, raw[1]);
+        multiply(kb, raw[0]);
+        if (kb + 1 < kb_end) {
+            if (kb + 2 < kb_end) fetch(kb + 2, raw[0]);
+            multiply(kb + 1, raw[1]);
         }
     }
 #pragma unroll
@@ -427,7 +440,15 @@ __global__ __launch_bounds__(kThreads) void ap_row_final_kernel(APParams p, int 
     const float *gp = p.Gpart + (size_t)rowl * ksp * (NACC * 1024);
     for (int i = tid; i < NACC * 1024; i += kThreads) {
         float g = 0.f;
-        for (int y = 0; y < ksp; ++y) g += gp[(size_t)y * (NACC * 1024) + i];
+        int y = 0;
+        for (; y + 8 <= ksp; y += 8) {   // eight loads in flight, added in order
+            float t[8];
+#pragma unroll
+            for (int k2 = 0; k2 < 8; ++k2) t[k2] = gp[(size_t)(y + k2) * (NACC * 1024) + i];
+#pragma unroll
+            for (int k2 = 0; k2 < 8; ++k2) g += t[k2];
+        }
+        for (; y < ksp; ++y) g += gp[(size_t)y * (NACC * 1024) + i];
         Gs[i] = g;
     }
     for (int l = tid; l < L; l += kThreads) Zs[l] = p.rowZt[(size_t)rowl * L + l];
@@ -473,8 +494,24 @@ __global__ __launch_bounds__(kThreads) void ap_reduce_kernel(APParams p, int u0)
     // the rows are added one by one to the running sum, so that the result does not depend on where
     // the batches are cut
     float cs = p.head_cos[o], ds = p.want_dist ? p.head_dist[o] : 0.f;
-    for (int r = r_lo; r < r_hi; ++r) {
-        const size_t rowl = (size_t)(u * p.NRG + r / rpg - p.grg0) * rpg + r % rpg;
+    auto rowl_of = [&](int r) -> size_t { return (size_t)(u * p.NRG + r / rpg - p.grg0) * rpg + r % rpg; };
+    int r = r_lo;
+    for (; r + 8 <= r_hi; r += 8) {   // eight rows in flight, added in order
+        float tc[8], td[8];
+#pragma unroll
+        for (int k2 = 0; k2 < 8; ++k2) {
+            const size_t rowl = rowl_of(r + k2);
+            tc[k2] = p.row_cos[rowl * LL + e];
+            td[k2] = p.want_dist ? p.row_dist[rowl * LL + e] : 0.f;
+        }
+#pragma unroll
+        for (int k2 = 0; k2 < 8; ++k2) {
+            cs += tc[k2];
+            ds += td[k2];
+        }
+    }
+    for (; r < r_hi; ++r) {
+        const size_t rowl = rowl_of(r);
         cs += p.row_cos[rowl * LL + e];
         if (p.want_dist) ds += p.row_dist[rowl * LL + e];
     }
@@ -500,6 +537,7 @@ __global__ void ap_final_kernel(int B, int L, int Hq, float inv_tokens, const fl
     const int b = (int)(idx / LL), e = (int)(idx % LL), i = e / L, j = e % L;
     const int lo = i > j ? e : j * L + i;   // the entry below the diagonal holds the sums
     float cs = 0.f, ds = 0.f;
+#pragma unroll 8
     for (int h = 0; h < Hq; ++h) {
         const size_t o = ((size_t)b * Hq + h) * LL;
         const float c = i == j ? 1.f : head_cos[o + lo] * inv_tokens;
@@ -588,12 +626,12 @@ __global__ __launch_bounds__(kSelThreads) void select_all_kernel(
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct APPlan {
-    int NW, NRG, NKB, nsplit, kps, total_rg, nrg_batch, ksp, kb_per;
+    int NW, NRG, NKB, nsplit, kps, tpw, total_rg, nrg_batch, ksp, kb_per;
     size_t head_cos_off, head_dist_off, rowm_off, rowz_off, rowzt_off, gpart_off, row_cos_off, row_dist_off, e_off, total_bytes;
     bool mfma;
 };
 
-constexpr int kGramTargetWorkgroups = 1024;
+constexpr int kGramTargetWorkgroups = 512;
 
 // Sizes for a batch of nrg row groups (NW, NRG, NKB, nsplit must be set).
 void ap_layout(const krul_shape_t *s, int nrg, APPlan *pl)
@@ -601,11 +639,11 @@ void ap_layout(const krul_shape_t *s, int nrg, APPlan *pl)
     const size_t L = s->n_layers, LL = L * L, NB = (L + 31) / 32, NACC = NB * (NB + 1) / 2;
     const size_t heads = (size_t)s->batch * s->n_q_heads * LL * sizeof(float);
     const size_t rows = (size_t)nrg * pl->NW * 32;
-    // the Gram kernel splits the keys until it has enough workgroups, but keeps at least 8 key blocks
+    // the Gram kernel splits the keys until it has enough workgroups, but keeps at least 16 key blocks
     // per workgroup so that the partial matrices stay small beside the weights
-    const long long row_wgs = (long long)nrg * pl->NW * (NB == 1 ? 1 : (NB == 2 ? 2 : 4));
+    const long long row_wgs = (long long)nrg * pl->NW * (NB == 1 ? 1 : (NB == 2 ? 2 : (NB == 3 ? 4 : 8)));
     long long ksp = (kGramTargetWorkgroups + row_wgs - 1) / row_wgs;
-    const long long ksp_max = pl->NKB / 8 > 1 ? pl->NKB / 8 : 1;
+    const long long ksp_max = pl->NKB / 16 > 1 ? pl->NKB / 16 : 1;
     if (ksp > ksp_max) ksp = ksp_max;
     if (ksp > 64) ksp = 64;
     pl->kb_per = (int)((pl->NKB + ksp - 1) / ksp);
@@ -619,13 +657,13 @@ void ap_layout(const krul_shape_t *s, int nrg, APPlan *pl)
     pl->gpart_off = off; off += align_up(rows * pl->ksp * NACC * 1024 * sizeof(float));
     pl->row_cos_off = off; off += align_up(rows * LL * sizeof(float));
     pl->row_dist_off = off; off += align_up(rows * LL * sizeof(float));
-    pl->e_off = off; off += align_up((size_t)nrg * pl->NW * L * (pl->NKB | 1) * 2048);
+    pl->e_off = off; off += align_up((size_t)nrg * pl->NW * L * pl->NKB * 2048);
     pl->total_bytes = off;
     pl->nrg_batch = nrg;
 }
 
 constexpr int kMaxLayersAllPairs = 128;
-constexpr size_t kDefaultBudget = (size_t)2 << 30;
+constexpr size_t kDefaultBudget = (size_t)4 << 30;
 
 // Validate and size: the largest batch of row groups whose workspace fits max_bytes (0: a default
 // budget), at least one group.  Returns a krul_status_t.
@@ -650,27 +688,34 @@ int ap_plan(const krul_shape_t *s, size_t max_bytes, APPlan *pl)
     if (pl->mfma) {
         pl->kps = kKeysPerSplit;
         pl->nsplit = (s->n_hist + kKeysPerSplit - 1) / kKeysPerSplit;
+        // a workgroup walks up to 8 splits, fewer while that leaves fewer than 2048 workgroups
+        const long long wg1 = total * s->n_layers;
+        long long tpw = wg1 * pl->nsplit / 2048;
+        pl->tpw = (int)(tpw < 1 ? 1 : (tpw > 8 ? 8 : tpw));
     } else {
         pl->nsplit = 1;
+        pl->tpw = 1;
         pl->kps = pl->NKB * 32;
     }
 
     const size_t budget = max_bytes ? max_bytes : kDefaultBudget;
-    ap_layout(s, 1, pl);
-    const size_t fixed = pl->rowm_off;   // the head sums do not grow with the batch
-    const size_t per_group = pl->total_bytes - fixed;
-    long long nrg = budget > fixed ? (long long)((budget - fixed) / per_group) : 0;
-    if (nrg < 1) nrg = 1;
-    if (nrg > total) nrg = total;
-    ap_layout(s, (int)nrg, pl);
-    while (pl->total_bytes > budget && nrg > 1) ap_layout(s, (int)--nrg, pl);   // (padding, partial matrices)
+    // the largest batch that fits (the size grows with the batch but for the partial matrices, whose
+    // number per row shrinks as the batch grows: bisect, then step down if need be)
+    long long lo = 1, hi = total;
+    while (lo < hi) {
+        const long long mid = (lo + hi + 1) / 2;
+        ap_layout(s, (int)mid, pl);
+        if (pl->total_bytes <= budget) lo = mid; else hi = mid - 1;
+    }
+    ap_layout(s, (int)lo, pl);
+    while (pl->total_bytes > budget && lo > 1) ap_layout(s, (int)--lo, pl);
     return KRUL_OK;
 }
 
 template <int D>
 void launch_weights(const APParams &p, hipStream_t st)
 {
-    const dim3 grid(p.nrg * p.L * p.nsplit);
+    const dim3 grid(p.nrg * p.L * ((p.nsplit + p.tpw - 1) / p.tpw));
     switch (p.NW) {
     case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1>), grid, dim3(64), 0, st, p); break;
     case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2>), grid, dim3(128), 0, st, p); break;
@@ -721,9 +766,9 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
     p.NW = pl.NW;
     p.NRG = pl.NRG;
     p.NKB = pl.NKB;
-    p.NKBs = pl.NKB | 1;
     p.nsplit = pl.nsplit;
     p.kps = pl.kps;
+    p.tpw = pl.tpw;
     p.want_dist = pair_dist != nullptr;
     p.E = ws + pl.e_off;
     p.rowM = reinterpret_cast<float *>(ws + pl.rowm_off);
@@ -760,10 +805,10 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
         }
         hipLaunchKernelGGL(ap_scale_kernel, dim3(rows), dim3(kThreads), 0, st, p);
         switch (NB) {
-        case 1: hipLaunchKernelGGL((ap_gram_kernel<1, 4>), dim3(rblocks, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
-        case 2: hipLaunchKernelGGL((ap_gram_kernel<2, 2>), dim3(rblocks * 2, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
-        case 3: hipLaunchKernelGGL((ap_gram_kernel<3, 1>), dim3(rblocks * 4, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
-        default: hipLaunchKernelGGL((ap_gram_kernel<4, 1>), dim3(rblocks * 4, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
+        case 1: hipLaunchKernelGGL((ap_gram_kernel<1, 4, 8>), dim3(rblocks, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
+        case 2: hipLaunchKernelGGL((ap_gram_kernel<2, 2, 8>), dim3(rblocks * 2, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
+        case 3: hipLaunchKernelGGL((ap_gram_kernel<3, 1, 8>), dim3(rblocks * 4, pl.ksp), dim3(512), 0, st, p, pl.ksp, pl.kb_per); break;
+        default: hipLaunchKernelGGL((ap_gram_kernel<4, 1, 4>), dim3(rblocks * 8, pl.ksp), dim3(256), 0, st, p, pl.ksp, pl.kb_per); break;
         }
         hipLaunchKernelGGL(ap_row_final_kernel, dim3(rows), dim3(kThreads), rf_smem, st, p, pl.ksp);
         const int u0 = g0 / p.NRG, u1 = (g0 + p.nrg - 1) / p.NRG;
