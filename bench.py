@@ -59,6 +59,48 @@ def cpu_baseline(w, seconds_target=15.0):
     }
 
 
+def all_pairs_bench(args, kr, torch, w, q, k, shp):
+    """One step = krul_all_pairs_similarity (cosine and distance of every two layers) + krul_select_pairs_all
+    on the distances.  The whole call is timed with events on the stream it runs on (torch's current one)."""
+    ws = torch.empty(kr.all_pairs_workspace_bytes(shp), dtype=torch.uint8, device="cuda")
+
+    def step():
+        out = kr.all_pairs_similarity(q, k, flags=args.flags, workspace=ws)
+        return kr.select_pairs_all(out["pair_dist"], w.n_select, True)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        pairs, _count = step()
+    e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    gpu_s = e0.elapsed_time(e1) * 1e-3 / args.steps
+    esz = 2 if w.dtype == "bf16" else 4
+    in_bytes = (w.q.size + w.k.size) * esz
+    weights_bytes = w.B * w.Hq * w.Tq * w.L * ((w.S + 31) // 32 * 32) * 2   # fp16 attention weights, written once, read once
+    res = {
+        "metric": "all-pairs layer similarity throughput", "value": w.score_elems / (dt / args.steps) / 1e9,
+        "unit": "Gscore-elems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} L={w.L} Hq/Hkv={w.Hq}/{w.Hkv} d={w.d} S={w.S} Tq={w.Tq} "
+                               f"{w.dtype}, all {w.L * (w.L - 1) // 2} layer pairs, select {w.n_select}",
+                   "score_elems": w.score_elems, "outputs": "pair_score_all+pair_dist_all", "workspace_bytes": ws.numel()},
+        # the design's own traffic: inputs once, the fp16 weights out and back
+        "roofline": {"bound": "hbm", "achieved": (in_bytes + 2 * weights_bytes) / gpu_s / 1e9, "peak": 8000.0,
+                     "unit": "GB/s", "frac": (in_bytes + 2 * weights_bytes) / gpu_s / 1e9 / 8000.0, "traffic": None,
+                     "kernel": "whole call (weights, scale, Gram, row, reduce kernels)", "kernel_us": gpu_s * 1e6,
+                     "algorithmic_bytes": in_bytes + 2 * weights_bytes, "input_bytes": in_bytes},
+        "selected_pairs": pairs.cpu().tolist()[0],
+    }
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +111,9 @@ def main():
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--with-dist", action="store_true",
                     help="also ask for the Euclidean distance by-product (pair_dist)")
+    ap.add_argument("--all-pairs", action="store_true",
+                    help="time the all-pairs reading instead (every two layers scored, then the greedy choice "
+                         "over all of them); not the headline metric")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run the library's plain copy kernel on MIB MiB a few times (a known-size "
                          "reference for rocprofv3 traffic counters)")
@@ -97,6 +142,9 @@ def main():
         k = torch.from_numpy(w.k.view(np.int16)).cuda().view(torch.bfloat16)
 
     shp = kr.make_shape(q, k, 0.0, args.flags)
+    if args.all_pairs:
+        all_pairs_bench(args, kr, torch, w, q, k, shp)
+        return
     ws = torch.empty(kr.workspace_bytes(shp), dtype=torch.uint8, device="cuda")
     out = {
         "pair_score": torch.empty((w.B, w.L - 1), dtype=torch.float32, device="cuda"),

@@ -8,26 +8,32 @@
 // exponentials ARE written out -- as the paper itself keeps the attention weights (Sec. 5) -- in
 // fp16, in batches of rows sized to the workspace the caller gives:
 //
-//   1. weights kernel: per (128 rows of a unit, layer) two sweeps over the keys with
-//      v_mfma_f32_32x32x16_bf16 logits: the row maxima, then e = 2^(x - max) <= 1, Z = sum e, and
-//      the fp16 store of e.  One wave owns 32 rows and every key of them, so the maximum and Z need
-//      one exchange between the two half-waves and nothing else.  K chunks of 64 keys go through a
-//      double-buffered, XOR-swizzled LDS tile; the second sweep re-reads K from L2.
-//      Layout of E: [32-row block][layer][32-key block][row][32 x fp16]: the 2 KB that a wave's
-//      result block covers are contiguous (full-line stores), and the 64 bytes of one (row, layer,
-//      key block) are what one Gram operand fetch reads.  Inside the 64 bytes the keys stand in the
-//      order of the MFMA result registers; the order is the same for all layers of a row, which is
-//      all a contraction over the keys needs.
-//   2. Gram kernel: one workgroup per row, its four waves taking every fourth key block:
-//      v_mfma_f32_32x32x16_f16 with A = B = the row's [32 layers x 16 keys] piece (lane = layer),
-//      one accumulator block per pair of 32-layer blocks.  The waves' sums are added in a fixed
-//      order in LDS; cos_ij = G_ij / sqrt(G_ii G_jj) and
-//      dist_ij^2 = G_ii/Z_i^2 + G_jj/Z_j^2 - 2 G_ij/(Z_i Z_j) are written per row.
-//   3. reduce kernel: per (unit, head of the group) the batch's rows are added, in order, to the
-//      head sums; the last kernel divides by the token count, averages the heads (Sec. 4.2) and
-//      mirrors the matrix.
-// A portable weights kernel (one wave per row and layer, fp32 dot products) covers fp32 inputs and
-// other head sizes; it writes the same layout.
+//   1. weights kernel: a workgroup of NW waves owns NW 32-row blocks of a unit (NW = 1, 2 or 4 with
+//      the rows a kv head has), one layer, and a run of key splits of 128 keys.  Per split: the keys
+//      go to one of two XOR-swizzled LDS buffers (the next split's are already in flight: through
+//      registers for NW = 4, by buffer_load ... lds for the narrow workgroups), one barrier,
+//      v_mfma_f32_32x32x16_bf16 logits of all 128 keys into registers, their maximum m (one exchange
+//      between the two half-waves: a wave owns all 128 keys of its 32 rows), e = 2^(x - m) <= 1,
+//      Z = sum e, and the fp16 store of e.  m and Z are kept per (row, layer, split).
+//      Layout of E: [32-row block][32-key block][layer][row][32 x fp16]: the 2 KB that a wave's
+//      result block covers are contiguous (full-line stores), the L x 2 KB of a key block are
+//      contiguous for the Gram kernel, and the 64 bytes of one (row, layer, key block) are what one
+//      Gram operand fetch reads.  Inside the 64 bytes the keys stand in the order of the MFMA result
+//      registers; the order is the same for all layers of a row, which is all a contraction over
+//      the keys needs.
+//   2. scale kernel: per (row, layer) the splits' exponents are replaced by their factors to the
+//      largest, 2^(m_s - max), and Z is summed at that common exponent.
+//   3. Gram kernel: a workgroup takes the rows of a 32-row block (each wave a few) and a range of
+//      key blocks; v_mfma_f32_32x32x16_f16 with A = B = the row's [32 layers x 16 keys] piece
+//      (lane = layer) scaled by the split's factor, one accumulator block per pair of 32-layer
+//      blocks; the partial matrices of the key ranges are written out.
+//   4. row kernel: per row the partial matrices are added in order; cos_ij = G_ij / sqrt(G_ii G_jj)
+//      and dist_ij^2 = G_ii/Z_i^2 + G_jj/Z_j^2 - 2 G_ij/(Z_i Z_j).
+//   5. reduce kernel: per (unit, head of the group) the batch's rows are added, one by one, to the
+//      head sums (so the result does not depend on the batch size); the last kernel divides by the
+//      token count, averages the heads (Sec. 4.2) and mirrors the matrix.
+// A portable weights kernel (one wave per row and layer, fp32 dot products, no key splits) covers
+// fp32 inputs and other head sizes; it writes the same layout.
 //
 // Also here: the greedy disjoint choice over all candidate pairs (Alg. 1, second loop).
 #include <math.h>
@@ -65,7 +71,7 @@ struct APParams {
     float *Gpart;       // [nrg*NW*32][ksp][NACC*1024] partial Gram matrices, result-register order
     float *row_cos;     // [nrg*NW*32][L*L]  (entries i > j)
     float *row_dist;    // same, or unused
-    float *head_cos;    // [B][Hq][L*L] running sums over the rows of a head
+    float *head_cos;    // [B][Hq][kClasses][L*L] running sums over the rows of a head, by class of token index
     float *head_dist;
 };
 
@@ -117,12 +123,37 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
     // buffer afterwards.  piece id = i*NT + tid -> key row id / PPR, 16-byte piece id % PPR.
     const int t0 = kc * p.tpw, t1 = min(p.nsplit, t0 + p.tpw);
     const uint16_t *klayer = static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S) * D;
-    uint4 stage[NLD];
+    // Narrow workgroups (NW < 4) would need too many staging registers per lane: they copy
+    // HBM -> LDS directly instead (buffer_load ... lds): wave-instruction j fills the 1 KB at j*1024
+    // (RPI key rows), lane by lane, so each lane fetches the 16-byte piece that belongs at its LDS
+    // position (the XOR swizzle applied on the global side); rows past the split's end are outside
+    // the descriptor's range and read as zero.
+    constexpr bool DMA = NW < 4;
+    constexpr int RPI = 64 / PPR, NI = KR / RPI / NW;
+    auto copy_keys = [&](int t, int buf) __attribute__((always_inline)) {
+#if defined(__HIP_DEVICE_COMPILE__)   // (the host pass only needs the kernel's launch stub)
+        const int kn = min(KR, S - t * KR);
+        const uintptr_t ka = (uintptr_t)(klayer + (size_t)t * KR * D);   // wave-uniform: a scalar descriptor
+        const uint16_t *kb_u = (const uint16_t *)(((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(ka >> 32)) << 32) |
+                                                  (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)ka));
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(kb_u), 0, __builtin_amdgcn_readfirstlane(kn * ROWB), 0x00020000);
+#pragma unroll
+        for (int jj = 0; jj < NI; ++jj) {
+            const int j = __builtin_amdgcn_readfirstlane(w) * NI + jj;
+            const int row = j * RPI + lane / PPR, pos = lane % PPR;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rsrc, (__attribute__((address_space(3))) void *)(&kl[buf][0] + j * 1024), 16,
+                row * ROWB + ((pos ^ swz<D>(row)) << 4), 0, 0, 0);
+        }
+#endif
+    };
+    uint4 stage[DMA ? 1 : NLD];
     auto fetch = [&](int t) __attribute__((always_inline)) {
         const int kn = min(KR, S - t * KR);
         const uint16_t *kbase = klayer + (size_t)t * KR * D;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
+        for (int i = 0; i < (DMA ? 0 : NLD); ++i) {
             const int id = i * NT + tid, row = id / PPR, pc = id % PPR;
             stage[i] = row < kn ? *reinterpret_cast<const uint4 *>(kbase + (size_t)row * D + pc * 8)
                                 : make_uint4(0u, 0u, 0u, 0u);
@@ -130,12 +161,15 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
     };
     auto put = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
+        for (int i = 0; i < (DMA ? 0 : NLD); ++i) {
             const int id = i * NT + tid, row = id / PPR, pc = id % PPR;
             *reinterpret_cast<uint4 *>(&kl[buf][row * ROWB + ((pc ^ swz<D>(row)) << 4)]) = stage[i];
         }
     };
-    fetch(t0);
+    if (DMA)
+        copy_keys(t0, 0);
+    else
+        fetch(t0);
     // query rows of a unit are contiguous in r: [b][l][kvh*g + r / Tq][r % Tq][D]
     const uint16_t *Qg = static_cast<const uint16_t *>(p.q);
     const uint16_t *qrow = Qg + ((((size_t)b * p.L + l) * p.Hq + (size_t)kvh * p.g) * p.Tq + (size_t)(row_ok ? r : 0)) * D;
@@ -149,10 +183,18 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
 
     for (int t = t0; t < t1; ++t) {
         const int buf = (t - t0) & 1;
-        put(buf);
+        if (DMA)
+            __builtin_amdgcn_s_waitcnt(0);   // this wave's part of split t has landed (and its stores are done)
+        else
+            put(buf);
         // the keys of split t are in LDS; every wave has finished reading the other buffer (split t-1)
         __syncthreads();
-        if (t + 1 < t1) fetch(t + 1);
+        if (t + 1 < t1) {
+            if (DMA)
+                copy_keys(t + 1, buf ^ 1);
+            else
+                fetch(t + 1);
+        }
         if (!blk_ok) continue;
 
         const int k0 = t * KR, kn = min(KR, S - k0), nkb = (kn + 31) / 32;
@@ -274,7 +316,7 @@ __global__ __launch_bounds__(64) void ap_weights_generic_kernel(APParams p)
     }
 }
 
-// Between the two: the key splits' exponents of a (row, layer) are replaced by their factors
+// 2. The key splits' exponents of a (row, layer) are replaced by their factors
 // against the largest, 2^(m_s - max m), and Z is summed at that common exponent.  One workgroup
 // per row of the batch.
 __global__ __launch_bounds__(kThreads) void ap_scale_kernel(APParams p)
@@ -313,7 +355,7 @@ __global__ __launch_bounds__(kThreads) void ap_scale_kernel(APParams p)
 }
 
 // ------------------------------------------------------------------------------------------------
-// 2. Gram kernel.  A workgroup of WV waves takes WV*RPW rows of one 32-row block (wave w the rows
+// 3. Gram kernel.  A workgroup of WV waves takes WV*RPW rows of one 32-row block (wave w the rows
 // w*RPW ..) and the key blocks [y*kb_per, (y+1)*kb_per) of them: all its waves walk the same key
 // blocks at about the same time, so that what it fetches of a (layer, key block) is one contiguous
 // run.  NB = 32-layer blocks (L <= 32*NB).  The sums go to Gpart[row][y] in result-register order
@@ -424,8 +466,8 @@ __global__ __launch_bounds__(WV * 64) void ap_gram_kernel(APParams p, int ksp, i
     }
 }
 
-// One workgroup per row of the batch: the row's partial Gram matrices are added in order, the key
-// splits' Z are brought to the common exponents, and cos_ij, dist_ij are written for i > j.
+// 4. One workgroup per row of the batch: the row's partial Gram matrices are added in order and
+// cos_ij, dist_ij are written for i > j.
 __global__ __launch_bounds__(kThreads) void ap_row_final_kernel(APParams p, int ksp)
 {
     extern __shared__ float sm_rf[];
@@ -474,11 +516,17 @@ __global__ __launch_bounds__(kThreads) void ap_row_final_kernel(APParams p, int 
 }
 
 // ------------------------------------------------------------------------------------------------
-// 3. rows -> head sums (one workgroup column per (unit of the batch, head of the group))
+// 5. rows -> head sums.  The rows of a head fall into kClasses classes by token index (t % kClasses);
+// a thread owns one matrix entry of one class of one head and adds that class's rows of the batch,
+// one by one in order, to the class's running sum: each sum sees its rows in the same order
+// wherever the batches are cut, so the result does not depend on the batch size.
+constexpr int kClasses = 8;
+
 __global__ __launch_bounds__(kThreads) void ap_reduce_kernel(APParams p, int u0)
 {
     const int LL = p.L * p.L;
     const int e = blockIdx.y * kThreads + threadIdx.x;
+    const int cls = blockIdx.z;
     const int hg = blockIdx.x % p.g, u = u0 + blockIdx.x / p.g;
     // rows of unit u that this batch holds, and those of them that belong to head hg
     const int rg_lo = max(p.grg0, u * p.NRG) - u * p.NRG;
@@ -490,27 +538,26 @@ __global__ __launch_bounds__(kThreads) void ap_reduce_kernel(APParams p, int u0)
     const int i = e / p.L, j = e % p.L;
     if (i <= j) return;
     const int b = u / p.Hkv, hq = (u % p.Hkv) * p.g + hg;
-    const size_t o = ((size_t)b * p.Hq + hq) * LL + e;
-    // the rows are added one by one to the running sum, so that the result does not depend on where
-    // the batches are cut
+    const size_t o = (((size_t)b * p.Hq + hq) * kClasses + cls) * LL + e;
     float cs = p.head_cos[o], ds = p.want_dist ? p.head_dist[o] : 0.f;
     auto rowl_of = [&](int r) -> size_t { return (size_t)(u * p.NRG + r / rpg - p.grg0) * rpg + r % rpg; };
-    int r = r_lo;
-    for (; r + 8 <= r_hi; r += 8) {   // eight rows in flight, added in order
-        float tc[8], td[8];
+    // first row of the range whose token index t = r - hg*Tq is in this class
+    int r = r_lo + ((cls - (r_lo - hg * p.Tq)) % kClasses + kClasses) % kClasses;
+    for (; r + 3 * kClasses < r_hi; r += 4 * kClasses) {   // four rows in flight, added in order
+        float tc[4], td[4];
 #pragma unroll
-        for (int k2 = 0; k2 < 8; ++k2) {
-            const size_t rowl = rowl_of(r + k2);
+        for (int k2 = 0; k2 < 4; ++k2) {
+            const size_t rowl = rowl_of(r + k2 * kClasses);
             tc[k2] = p.row_cos[rowl * LL + e];
             td[k2] = p.want_dist ? p.row_dist[rowl * LL + e] : 0.f;
         }
 #pragma unroll
-        for (int k2 = 0; k2 < 8; ++k2) {
+        for (int k2 = 0; k2 < 4; ++k2) {
             cs += tc[k2];
             ds += td[k2];
         }
     }
-    for (; r < r_hi; ++r) {
+    for (; r < r_hi; r += kClasses) {
         const size_t rowl = rowl_of(r);
         cs += p.row_cos[rowl * LL + e];
         if (p.want_dist) ds += p.row_dist[rowl * LL + e];
@@ -526,27 +573,51 @@ __global__ void ap_fill_kernel(float *ptr, size_t n, float v)
 }
 
 // head sums -> means over tokens, average over heads, mirrored matrices with cos 1 / distance 0 on
-// the diagonal.  One thread per (conversation, i, j).
-__global__ void ap_final_kernel(int B, int L, int Hq, float inv_tokens, const float *__restrict__ head_cos,
-                                const float *__restrict__ head_dist, float *__restrict__ pair_cos,
-                                float *__restrict__ pair_dist, float *__restrict__ head_out)
+// the diagonal.  A workgroup takes 8 entries (conversation, i, j); 32 threads share an entry's heads
+// (h = lane, lane + 32, ...) and their sums are added in lane order.
+__global__ __launch_bounds__(kThreads) void ap_final_kernel(int B, int L, int Hq, float inv_tokens,
+                                                            const float *__restrict__ head_cos,
+                                                            const float *__restrict__ head_dist,
+                                                            float *__restrict__ pair_cos, float *__restrict__ pair_dist,
+                                                            float *__restrict__ head_out)
 {
+    __shared__ float sc[32][8], sd[32][8];
     const int LL = L * L;
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)B * LL) return;
-    const int b = (int)(idx / LL), e = (int)(idx % LL), i = e / L, j = e % L;
-    const int lo = i > j ? e : j * L + i;   // the entry below the diagonal holds the sums
+    const int el = threadIdx.x & 7, hl = threadIdx.x >> 3;
+    const size_t idx = (size_t)blockIdx.x * 8 + el;
+    const bool ok = idx < (size_t)B * LL;
     float cs = 0.f, ds = 0.f;
-#pragma unroll 8
-    for (int h = 0; h < Hq; ++h) {
-        const size_t o = ((size_t)b * Hq + h) * LL;
-        const float c = i == j ? 1.f : head_cos[o + lo] * inv_tokens;
-        cs += c;
-        if (head_out) head_out[o + e] = c;
-        if (pair_dist) ds += i == j ? 0.f : head_dist[o + lo] * inv_tokens;
+    if (ok) {
+        const int b = (int)(idx / LL), e = (int)(idx % LL), i = e / L, j = e % L;
+        const int lo = i > j ? e : j * L + i;   // the entry below the diagonal holds the sums
+        for (int h = hl; h < Hq; h += 32) {
+            const size_t o = ((size_t)b * Hq + h) * LL, oc = o * kClasses + lo;
+            float hc = 0.f, hd = 0.f;   // the classes' sums, in order
+            if (i != j) {
+#pragma unroll
+                for (int cl = 0; cl < kClasses; ++cl) {
+                    hc += head_cos[oc + (size_t)cl * LL];
+                    if (pair_dist) hd += head_dist[oc + (size_t)cl * LL];
+                }
+            }
+            const float c = i == j ? 1.f : hc * inv_tokens;
+            cs += c;
+            if (head_out) head_out[o + e] = c;
+            ds += hd * inv_tokens;
+        }
     }
-    pair_cos[idx] = cs / (float)Hq;
-    if (pair_dist) pair_dist[idx] = ds / (float)Hq;
+    sc[hl][el] = cs;
+    sd[hl][el] = ds;
+    __syncthreads();
+    if (ok && hl == 0) {
+        float c = 0.f, d = 0.f;
+        for (int k2 = 0; k2 < 32; ++k2) {
+            c += sc[k2][el];
+            d += sd[k2][el];
+        }
+        pair_cos[idx] = c / (float)Hq;
+        if (pair_dist) pair_dist[idx] = d / (float)Hq;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -637,7 +708,7 @@ constexpr int kGramTargetWorkgroups = 512;
 void ap_layout(const krul_shape_t *s, int nrg, APPlan *pl)
 {
     const size_t L = s->n_layers, LL = L * L, NB = (L + 31) / 32, NACC = NB * (NB + 1) / 2;
-    const size_t heads = (size_t)s->batch * s->n_q_heads * LL * sizeof(float);
+    const size_t heads = (size_t)s->batch * s->n_q_heads * kClasses * LL * sizeof(float);
     const size_t rows = (size_t)nrg * pl->NW * 32;
     // the Gram kernel splits the keys until it has enough workgroups, but keeps at least 16 key blocks
     // per workgroup so that the partial matrices stay small beside the weights
@@ -781,7 +852,7 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
     p.head_dist = reinterpret_cast<float *>(ws + pl.head_dist_off);
 
     const int L = p.L, LL = L * L;
-    const size_t n_head = (size_t)p.B * p.Hq * LL;
+    const size_t n_head = (size_t)p.B * p.Hq * kClasses * LL;
     hipLaunchKernelGGL(ap_fill_kernel, dim3((unsigned)((n_head + 255) / 256)), dim3(256), 0, st, p.head_cos, n_head, 0.f);
     if (p.want_dist)
         hipLaunchKernelGGL(ap_fill_kernel, dim3((unsigned)((n_head + 255) / 256)), dim3(256), 0, st, p.head_dist, n_head, 0.f);
@@ -812,12 +883,12 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
         }
         hipLaunchKernelGGL(ap_row_final_kernel, dim3(rows), dim3(kThreads), rf_smem, st, p, pl.ksp);
         const int u0 = g0 / p.NRG, u1 = (g0 + p.nrg - 1) / p.NRG;
-        hipLaunchKernelGGL(ap_reduce_kernel, dim3((u1 - u0 + 1) * p.g, (LL + kThreads - 1) / kThreads), dim3(kThreads),
+        hipLaunchKernelGGL(ap_reduce_kernel, dim3((u1 - u0 + 1) * p.g, (LL + kThreads - 1) / kThreads, kClasses), dim3(kThreads),
                            0, st, p, u0);
         if (hipGetLastError() != hipSuccess) return KRUL_ELAUNCH;
     }
     const size_t n_out = (size_t)p.B * LL;
-    hipLaunchKernelGGL(ap_final_kernel, dim3((unsigned)((n_out + 255) / 256)), dim3(256), 0, st, p.B, L, p.Hq,
+    hipLaunchKernelGGL(ap_final_kernel, dim3((unsigned)((n_out + 7) / 8)), dim3(kThreads), 0, st, p.B, L, p.Hq,
                        1.0f / (float)p.Tq, p.head_cos, p.head_dist, pair_score, pair_dist, head_score);
     return hipGetLastError() == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
 }
