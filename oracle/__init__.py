@@ -165,6 +165,19 @@ def all_pairs(q: np.ndarray, k: np.ndarray, scale=None, causal=False) -> dict:
     return out
 
 
+def all_pairs_heads(q: np.ndarray, k: np.ndarray, heads, scale=None, causal=False):
+    """The all-pairs matrices of chosen (b, h) heads only: (head_cos [n,L,L], head_dist [n,L,L])."""
+    q, k, shp = _prep(q, k, scale, causal)
+    heads = np.ascontiguousarray(np.asarray(heads, dtype=np.int32).reshape(-1, 2))
+    n, L = heads.shape[0], shp.n_layers
+    hc, hd = np.empty((n, L, L)), np.empty((n, L, L))
+    rc = _load().krul_oracle_all_pairs_heads(ctypes.byref(shp), _ptr(q), _ptr(k), ctypes.c_int(n), _ptr(heads),
+                                             _ptr(hc), _ptr(hd))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return hc, hd
+
+
 def select_pairs_all(score, n_select: int, closer_is_smaller: bool, eligible=None):
     """Greedy disjoint choice over every two layers (Alg. 1).  score [B,L,L] (lower triangle read) ->
     (pairs [B,n_select,2] int32 as (j, i), j < i, padded with -1; count [B] int32)."""

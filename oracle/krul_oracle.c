@@ -333,48 +333,72 @@ int krul_oracle_ir_mass(const oracle_shape_t *s, const void *q, const void *k,
  *   pair_cos / pair_dist : [B][L][L]       (may be NULL)
  * All are symmetric; the diagonal holds cos 1 and distance 0 (a row against itself).
  */
+/* One (conversation b, query head h): c_out, d_out [L][L] as described above. */
+static void head_all_pairs(const oracle_shape_t *s, const void *q, const void *k, int b, int h,
+                           double *c_out, double *d_out)
+{
+    const int L = s->n_layers, S = s->n_hist, Tq = s->n_query;
+    /* the attention weights of all layers for this head, stored: P[l][t][j] */
+    double *P = (double *)malloc(sizeof(double) * (size_t)L * Tq * S);
+    for (int l = 0; l < L; ++l)
+        attention_weights(s, q, k, b, l, h, P + (size_t)l * Tq * S);
+    for (int i = 0; i < L; ++i) {
+        c_out[(size_t)i * L + i] = 1.0;
+        d_out[(size_t)i * L + i] = 0.0;
+        for (int j = 0; j < i; ++j) {
+            double csum = 0.0, dsum = 0.0;
+            for (int t = 0; t < Tq; ++t) {
+                const double *a = P + ((size_t)i * Tq + t) * S;
+                const double *c = P + ((size_t)j * Tq + t) * S;
+                double ab = 0.0, aa = 0.0, bb = 0.0, dd = 0.0;
+                for (int x = 0; x < S; ++x) {
+                    ab += a[x] * c[x];
+                    aa += a[x] * a[x];
+                    bb += c[x] * c[x];
+                    const double df = a[x] - c[x];
+                    dd += df * df;
+                }
+                csum += ab / (sqrt(aa) * sqrt(bb));
+                dsum += sqrt(dd);
+            }
+            c_out[(size_t)i * L + j] = c_out[(size_t)j * L + i] = csum / Tq;
+            d_out[(size_t)i * L + j] = d_out[(size_t)j * L + i] = dsum / Tq;
+        }
+    }
+    free(P);
+}
+
+/*
+ * The same for a chosen list of heads only: heads[2*u + {0,1}] = (b, h); head_cos / head_dist
+ * [n_heads][L][L].  Returns 0, or -1 on a bad argument.
+ */
+int krul_oracle_all_pairs_heads(const oracle_shape_t *s, const void *q, const void *k, int n_heads,
+                                const int32_t *heads, double *head_cos, double *head_dist)
+{
+    if (!shape_ok(s) || !q || !k || n_heads < 0 || (n_heads && (!heads || !head_cos || !head_dist)))
+        return -1;
+    for (int u = 0; u < n_heads; ++u)
+        if (heads[2 * u] < 0 || heads[2 * u] >= s->batch || heads[2 * u + 1] < 0 || heads[2 * u + 1] >= s->n_q_heads)
+            return -1;
+    const size_t LL = (size_t)s->n_layers * s->n_layers;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < n_heads; ++u)
+        head_all_pairs(s, q, k, heads[2 * u], heads[2 * u + 1], head_cos + (size_t)u * LL, head_dist + (size_t)u * LL);
+    return 0;
+}
+
 int krul_oracle_all_pairs(const oracle_shape_t *s, const void *q, const void *k,
                           double *pair_cos, double *pair_dist, double *head_cos, double *head_dist)
 {
     if (!shape_ok(s) || !q || !k)
         return -1;
-    const int B = s->batch, L = s->n_layers, H = s->n_q_heads, S = s->n_hist, Tq = s->n_query;
+    const int B = s->batch, L = s->n_layers, H = s->n_q_heads;
     const size_t LL = (size_t)L * L;
     double *hc = (double *)malloc(sizeof(double) * (size_t)B * H * LL);
     double *hd = (double *)malloc(sizeof(double) * (size_t)B * H * LL);
 #pragma omp parallel for schedule(dynamic, 1)
-    for (int bh = 0; bh < B * H; ++bh) {
-        const int b = bh / H, h = bh % H;
-        /* the attention weights of all layers for this head, stored: P[l][t][j] */
-        double *P = (double *)malloc(sizeof(double) * (size_t)L * Tq * S);
-        for (int l = 0; l < L; ++l)
-            attention_weights(s, q, k, b, l, h, P + (size_t)l * Tq * S);
-        double *c_out = hc + (size_t)bh * LL, *d_out = hd + (size_t)bh * LL;
-        for (int i = 0; i < L; ++i) {
-            c_out[(size_t)i * L + i] = 1.0;
-            d_out[(size_t)i * L + i] = 0.0;
-            for (int j = 0; j < i; ++j) {
-                double csum = 0.0, dsum = 0.0;
-                for (int t = 0; t < Tq; ++t) {
-                    const double *a = P + ((size_t)i * Tq + t) * S;
-                    const double *c = P + ((size_t)j * Tq + t) * S;
-                    double ab = 0.0, aa = 0.0, bb = 0.0, dd = 0.0;
-                    for (int x = 0; x < S; ++x) {
-                        ab += a[x] * c[x];
-                        aa += a[x] * a[x];
-                        bb += c[x] * c[x];
-                        const double df = a[x] - c[x];
-                        dd += df * df;
-                    }
-                    csum += ab / (sqrt(aa) * sqrt(bb));
-                    dsum += sqrt(dd);
-                }
-                c_out[(size_t)i * L + j] = c_out[(size_t)j * L + i] = csum / Tq;
-                d_out[(size_t)i * L + j] = d_out[(size_t)j * L + i] = dsum / Tq;
-            }
-        }
-        free(P);
-    }
+    for (int bh = 0; bh < B * H; ++bh)
+        head_all_pairs(s, q, k, bh / H, bh % H, hc + (size_t)bh * LL, hd + (size_t)bh * LL);
     for (int b = 0; b < B; ++b)
         for (size_t e = 0; e < LL; ++e) {
             double cs = 0.0, ds = 0.0;

@@ -145,3 +145,47 @@ def test_all_pairs_then_selection_end_to_end(G, oracle):
         tri = want["pair_dist"][b][np.tril_indices(L, -1)]
         if np.min(np.diff(np.sort(tri))) > 2 * G.TOL:
             np.testing.assert_array_equal(pairs.cpu().numpy()[b], ep[b])
+
+
+def full_size_sample(G, oracle, w, heads, name, **kw):
+    """All-pairs at a benchmark configuration's size: the matrices of a few sampled heads are computed
+    by the oracle (all query rows, all keys, all layer pairs) and compared entry by entry; properties
+    are checked on the whole output."""
+    import paper_2507_08045_amd as kr
+    q, k = G.to_device(w)
+    got = gpu_all_pairs(q, k, **kw)
+    hs, ps, pd = got["head_score"], got["pair_score"], got["pair_dist"]
+    assert np.all(np.isfinite(hs)) and np.all(hs > 0) and np.all(hs <= 1 + 1e-5)
+    assert np.all(pd >= 0) and np.all(pd <= np.sqrt(2) + 1e-5)
+    np.testing.assert_allclose(ps, hs.mean(axis=1), atol=1e-6)          # head average
+    np.testing.assert_array_equal(ps, np.swapaxes(ps, 1, 2))
+    hc, _ = oracle.all_pairs_heads(w.q, w.k, heads)
+    err = max(np.max(np.abs(hs[b, h] - hc[u])) for u, (b, h) in enumerate(heads))
+    print(f"[{name}] {len(heads)} sampled heads x {w.L * (w.L - 1) // 2} pairs: max |gpu - oracle| = {err:.2e}", flush=True)
+    assert err <= G.TOL
+    # selection over all pairs on the GPU's own distances: device == oracle selector, bit for bit
+    pairs, count = kr.select_pairs_all(torch.from_numpy(pd).cuda(), w.n_select, True)
+    wp, wc = oracle.select_pairs_all(pd.astype(np.float64), w.n_select, True)
+    np.testing.assert_array_equal(pairs.cpu().numpy(), wp)
+    np.testing.assert_array_equal(count.cpu().numpy(), wc)
+    return got
+
+
+def test_all_pairs_c2_full_size(G, oracle):
+    full_size_sample(G, oracle, workloads.config("C2"), [(0, 5), (0, 18), (0, 31)], "C2 all pairs")
+
+
+def test_all_pairs_c3_full_size(G, oracle):
+    full_size_sample(G, oracle, workloads.config("C3"), [(0, 9), (0, 30)], "C3 all pairs")
+
+
+def test_all_pairs_c4_shape_in_batches(G, oracle):
+    """C4's layer / head / history shape with 128 query tokens (the oracle keeps a head's weights of all
+    layers: 8192 x 2048 rows would be 4 GiB and minutes), in batches of a quarter of the rows."""
+    import paper_2507_08045_amd as kr
+    w = workloads.scaled("C4", Tq=128)
+    q, k = G.to_device(w)
+    shp = kr.make_shape(q, k)
+    budget = kr.all_pairs_workspace_bytes(shp) // 4
+    assert kr.all_pairs_workspace_bytes(shp, budget) <= budget
+    full_size_sample(G, oracle, w, [(0, 13)], "C4 shape, Tq=128, four batches", max_workspace_bytes=budget)

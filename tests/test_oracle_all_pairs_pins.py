@@ -58,6 +58,16 @@ def test_matches_scipy_softmax_and_cdist(oracle):
         np.testing.assert_allclose(got["pair_dist"], dist.mean(1), rtol=0, atol=1e-9)
 
 
+def test_chosen_heads_are_the_same_numbers(oracle):
+    rng = np.random.default_rng(38)
+    q, k = rand_qk(rng, 2, 4, 4, 2, 8, 11, 3)
+    full = oracle.all_pairs(q, k)
+    hc, hd = oracle.all_pairs_heads(q, k, [(1, 3), (0, 0), (1, 0)])
+    for u, (b, h) in enumerate([(1, 3), (0, 0), (1, 0)]):
+        np.testing.assert_array_equal(hc[u], full["head_score"][b, h])
+        np.testing.assert_array_equal(hd[u], full["head_dist"][b, h])
+
+
 def test_symmetric_unit_diagonal_and_bounds(oracle):
     rng = np.random.default_rng(32)
     q, k = rand_qk(rng, 2, 6, 4, 2, 16, 40, 4)
