@@ -49,6 +49,7 @@ typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kThreads = 256;
+constexpr int kDumpBlocks = 128;     // 2 KB blocks of the area that takes stores with no place of their own
 constexpr int kKeysPerSplit = 128;   // keys of one step of a weights-kernel workgroup (an LDS buffer)
 
 struct APParams {
@@ -64,6 +65,7 @@ struct APParams {
     int tpw;            // key splits that one weights-kernel workgroup walks
     int grg0, nrg;      // this batch: global row groups [grg0, grg0 + nrg)
     int want_dist;
+    unsigned char *dump;   // [kDumpBlocks][2 KB]
     unsigned char *E;   // [nrg*NW][NKB][L][32][64 bytes]; e = 2^(x - m) with m of the row, layer and key split
     float *rowM;        // [nrg*NW*32][nsplit][L]  reference exponent m; then the factor 2^(m - largest m of the row, layer)
     float *rowZ;        // [nrg*NW*32][nsplit][L]  sum of e over the split's keys
@@ -99,12 +101,15 @@ __device__ inline uint32_t pack_f16(float a, float b)
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kernel(APParams p)
 {
-    constexpr int KS = D / 16, PPR = D / 8, ROWB = D * 2, KR = kKeysPerSplit, NKBW = KR / 32;
-    constexpr int NT = NW * 64, NLD = KR * PPR / NT;
+    constexpr int KS = D / 16, ROWB = D * 2, KR = kKeysPerSplit, NKBW = KR / 32;
+    [[maybe_unused]] constexpr int PPR = D / 8;
     __shared__ __attribute__((aligned(16))) unsigned char kl[2][KR * ROWB];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, n = lane & 31;
     const int nkc = (p.nsplit + p.tpw - 1) / p.tpw;   // workgroups along the keys
+    // key chunks vary fastest, then layers: the workgroups that run at the same time fill one row
+    // group's part of E densely (the order with the row groups fastest, which would share the keys
+    // between them, measured 20 % slower)
     const int kc = blockIdx.x % nkc;
     const int l = (blockIdx.x / nkc) % p.L;
     const int rgl = blockIdx.x / (nkc * p.L);
@@ -113,25 +118,21 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
     const int b = u / p.Hkv, kvh = u % p.Hkv;
     const int rbl = rgl * NW + w;
     const int r = (rg * NW + w) * 32 + n;            // row of the unit: head-in-group * Tq + t
-    const bool blk_ok = (rg * NW + w) * 32 < p.Rk;   // this wave has rows at all
     const bool row_ok = r < p.Rk;
     const int S = p.S;
     const int row_end = row_ok ? (p.causal ? S - p.Tq + r % p.Tq + 1 : S) : 0;   // keys [0, row_end) are seen
 
     // This workgroup walks the key splits [t0, t1) of its rows and layer, KR keys each.  The keys of
-    // split t+1 are fetched into registers while split t is worked on, and written to the other LDS
-    // buffer afterwards.  piece id = i*NT + tid -> key row id / PPR, 16-byte piece id % PPR.
+    // split t+1 are copied into the other LDS buffer while split t is worked on.
     const int t0 = kc * p.tpw, t1 = min(p.nsplit, t0 + p.tpw);
-    const uint16_t *klayer = static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S) * D;
-    // Narrow workgroups (NW < 4) would need too many staging registers per lane: they copy
-    // HBM -> LDS directly instead (buffer_load ... lds): wave-instruction j fills the 1 KB at j*1024
-    // (RPI key rows), lane by lane, so each lane fetches the 16-byte piece that belongs at its LDS
-    // position (the XOR swizzle applied on the global side); rows past the split's end are outside
-    // the descriptor's range and read as zero.
-    constexpr bool DMA = NW < 4;
-    constexpr int RPI = 64 / PPR, NI = KR / RPI / NW;
+    [[maybe_unused]] const uint16_t *klayer = static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S) * D;
+    // The keys go HBM -> LDS directly (buffer_load ... lds, no staging registers):
+    // wave-instruction j fills the 1 KB at j*1024 (RPI key rows), lane by lane, so each lane fetches
+    // the 16-byte piece that belongs at its LDS position (the XOR swizzle applied on the global
+    // side); rows past the split's end are outside the descriptor's range and read as zero.
     auto copy_keys = [&](int t, int buf) __attribute__((always_inline)) {
 #if defined(__HIP_DEVICE_COMPILE__)   // (the host pass only needs the kernel's launch stub)
+        constexpr int RPI = 64 / PPR, NI = KR / RPI / NW;
         const int kn = min(KR, S - t * KR);
         const uintptr_t ka = (uintptr_t)(klayer + (size_t)t * KR * D);   // wave-uniform: a scalar descriptor
         const uint16_t *kb_u = (const uint16_t *)(((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(ka >> 32)) << 32) |
@@ -148,28 +149,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
         }
 #endif
     };
-    uint4 stage[DMA ? 1 : NLD];
-    auto fetch = [&](int t) __attribute__((always_inline)) {
-        const int kn = min(KR, S - t * KR);
-        const uint16_t *kbase = klayer + (size_t)t * KR * D;
-#pragma unroll
-        for (int i = 0; i < (DMA ? 0 : NLD); ++i) {
-            const int id = i * NT + tid, row = id / PPR, pc = id % PPR;
-            stage[i] = row < kn ? *reinterpret_cast<const uint4 *>(kbase + (size_t)row * D + pc * 8)
-                                : make_uint4(0u, 0u, 0u, 0u);
-        }
-    };
-    auto put = [&](int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < (DMA ? 0 : NLD); ++i) {
-            const int id = i * NT + tid, row = id / PPR, pc = id % PPR;
-            *reinterpret_cast<uint4 *>(&kl[buf][row * ROWB + ((pc ^ swz<D>(row)) << 4)]) = stage[i];
-        }
-    };
-    if (DMA)
-        copy_keys(t0, 0);
-    else
-        fetch(t0);
+    copy_keys(t0, 0);
     // query rows of a unit are contiguous in r: [b][l][kvh*g + r / Tq][r % Tq][D]
     const uint16_t *Qg = static_cast<const uint16_t *>(p.q);
     const uint16_t *qrow = Qg + ((((size_t)b * p.L + l) * p.Hq + (size_t)kvh * p.g) * p.Tq + (size_t)(row_ok ? r : 0)) * D;
@@ -181,21 +161,20 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
         qf[ks] = __builtin_bit_cast(bf16x8, v);
     }
 
+    // The query rows and the first split's keys have arrived before the loop starts.  Inside it a
+    // split's copy is followed by the kStores stores of the split before it, all unconditional
+    // (addresses are redirected instead); memory operations complete in the order issued, so "at
+    // most kStores - 2 outstanding" means this wave's part of split t has landed, without waiting
+    // for the newest stores.
+    constexpr int kStores = 2 * NKBW + 2;
+    static_assert(kStores - 2 == 8, "the wait below is written for eight");
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     for (int t = t0; t < t1; ++t) {
         const int buf = (t - t0) & 1;
-        if (DMA)
-            __builtin_amdgcn_s_waitcnt(0);   // this wave's part of split t has landed (and its stores are done)
-        else
-            put(buf);
+        __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8)
         // the keys of split t are in LDS; every wave has finished reading the other buffer (split t-1)
         __syncthreads();
-        if (t + 1 < t1) {
-            if (DMA)
-                copy_keys(t + 1, buf ^ 1);
-            else
-                fetch(t + 1);
-        }
-        if (!blk_ok) continue;
+        if (t + 1 < t1) copy_keys(t + 1, buf ^ 1);
 
         const int k0 = t * KR, kn = min(KR, S - k0), nkb = (kn + 31) / 32;
         // logits of the 32 keys of block kb against this wave's 32 rows: lane (n, half) gets row n,
@@ -205,17 +184,21 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
         float mx = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < NKBW; ++kb) {
-            if (kb < nkb) {
+            {
                 f32x16 a;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) a[v] = 0.f;
                 const int row = kb * 32 + n;
                 const unsigned char *rp = &kl[buf][row * ROWB];
+                bf16x8 ka[KS];   // all operand reads first: one LDS latency per block, not one per MFMA
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(rp + (((2 * ks + half) ^ swz<D>(row)) << 4));
-                    a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], a, 0, 0, 0);
-                }
+                for (int ks = 0; ks < KS; ++ks)
+                    ka[ks] = *reinterpret_cast<const bf16x8 *>(rp + (((2 * ks + half) ^ swz<D>(row)) << 4));
+                // (the empty statements keep the compiler from moving the reads back between the MFMAs)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(ka[ks]));
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[ks], a, 0, 0, 0);
                 const int key0 = k0 + kb * 32;
                 if (__any(key0 + 32 > row_end)) {   // some row of the wave does not see all 32 keys
                     const int lim = row_end - key0 - 4 * half;
@@ -235,7 +218,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
         float z = 0.f;
 #pragma unroll
         for (int kb = 0; kb < NKBW; ++kb) {
-            if (kb < nkb) {
+            {
                 uint32_t pk[8];
 #pragma unroll
                 for (int v = 0; v < 16; v += 2) {
@@ -244,15 +227,18 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
                     z += e0 + e1;
                     pk[v >> 1] = pack_f16(e0, e1);
                 }
-                if (row_ok) {
-                    uint4 *dst = reinterpret_cast<uint4 *>(p.E + e_block_offset(p, rbl, l, t * NKBW + kb) + n * 64 + half * 32);
-                    dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-                    dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-                }
+                // a block past the last key has no place in E: its zeros go to a dump area.  Rows
+                // that do not exist (and the blocks of a wave without rows) have theirs and are
+                // never read.
+                unsigned char *blk = kb < nkb ? p.E + e_block_offset(p, rbl, l, t * NKBW + kb)
+                                              : p.dump + (size_t)((blockIdx.x * NW + w) & (kDumpBlocks - 1)) * 2048;
+                uint4 *dst = reinterpret_cast<uint4 *>(blk + n * 64 + half * 32);
+                dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
             }
         }
         z += __shfl_xor(z, 32, 64);
-        if (row_ok && half == 0) {
+        {   // (both half-waves hold the same values and write them to the same place)
             const size_t o = (((size_t)rbl * 32 + n) * p.nsplit + t) * p.L + l;
             p.rowM[o] = mx > -INFINITY ? M : kMInit;
             p.rowZ[o] = z;
@@ -698,7 +684,7 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct APPlan {
     int NW, NRG, NKB, nsplit, kps, tpw, total_rg, nrg_batch, ksp, kb_per;
-    size_t head_cos_off, head_dist_off, rowm_off, rowz_off, rowzt_off, gpart_off, row_cos_off, row_dist_off, e_off, total_bytes;
+    size_t head_cos_off, head_dist_off, dump_off, rowm_off, rowz_off, rowzt_off, gpart_off, row_cos_off, row_dist_off, e_off, total_bytes;
     bool mfma;
 };
 
@@ -722,6 +708,7 @@ void ap_layout(const krul_shape_t *s, int nrg, APPlan *pl)
     size_t off = 0;
     pl->head_cos_off = off; off += align_up(heads);
     pl->head_dist_off = off; off += align_up(heads);
+    pl->dump_off = off; off += align_up((size_t)kDumpBlocks * 2048);
     pl->rowm_off = off; off += align_up(rows * L * pl->nsplit * sizeof(float));
     pl->rowz_off = off; off += align_up(rows * L * pl->nsplit * sizeof(float));
     pl->rowzt_off = off; off += align_up(rows * L * sizeof(float));
@@ -842,6 +829,7 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
     p.tpw = pl.tpw;
     p.want_dist = pair_dist != nullptr;
     p.E = ws + pl.e_off;
+    p.dump = ws + pl.dump_off;
     p.rowM = reinterpret_cast<float *>(ws + pl.rowm_off);
     p.rowZ = reinterpret_cast<float *>(ws + pl.rowz_off);
     p.rowZt = reinterpret_cast<float *>(ws + pl.rowzt_off);
