@@ -58,7 +58,8 @@ struct APParams {
     int B, L, Hq, Hkv, g, d, S, Tq, Rk;
     int causal;
     float c;            // scale * log2(e)
-    int NW;             // 32-row blocks per row group = waves of a weights-kernel workgroup (1, 2 or 4)
+    int NW;             // 32-row blocks per row group (1, 2, 4 or 8: the waves of a weights-kernel workgroup
+                        // times the blocks each takes)
     int NRG;            // row groups per unit
     int NKB;            // 32-key blocks per row
     int nsplit, kps;    // key splits of the weights kernel, keys per split (a multiple of 32)
@@ -98,7 +99,9 @@ __device__ inline uint32_t pack_f16(float a, float b)
 
 // ------------------------------------------------------------------------------------------------
 // 1. weights kernel (bf16, head_dim 64 or 128)
-template <int D, int NW>
+// NW waves, each with RB 32-row blocks (taken one after the other against the same keys in LDS): a
+// row group is NW*RB blocks.
+template <int D, int NW, int RB>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kernel(APParams p)
 {
     constexpr int KS = D / 16, ROWB = D * 2, KR = kKeysPerSplit, NKBW = KR / 32;
@@ -116,11 +119,16 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
     const int grg = p.grg0 + rgl;
     const int u = grg / p.NRG, rg = grg % p.NRG;
     const int b = u / p.Hkv, kvh = u % p.Hkv;
-    const int rbl = rgl * NW + w;
-    const int r = (rg * NW + w) * 32 + n;            // row of the unit: head-in-group * Tq + t
-    const bool row_ok = r < p.Rk;
     const int S = p.S;
-    const int row_end = row_ok ? (p.causal ? S - p.Tq + r % p.Tq + 1 : S) : 0;   // keys [0, row_end) are seen
+    int rbl[RB], row_end[RB];
+    bool row_ok[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+        rbl[j] = (rgl * NW + w) * RB + j;
+        const int r = ((rg * NW + w) * RB + j) * 32 + n;   // row of the unit: head-in-group * Tq + t
+        row_ok[j] = r < p.Rk;
+        row_end[j] = row_ok[j] ? (p.causal ? S - p.Tq + r % p.Tq + 1 : S) : 0;   // keys [0, row_end) are seen
+    }
 
     // This workgroup walks the key splits [t0, t1) of its rows and layer, KR keys each.  The keys of
     // split t+1 are copied into the other LDS buffer while split t is worked on.
@@ -152,17 +160,21 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
     copy_keys(t0, 0);
     // query rows of a unit are contiguous in r: [b][l][kvh*g + r / Tq][r % Tq][D]
     const uint16_t *Qg = static_cast<const uint16_t *>(p.q);
-    const uint16_t *qrow = Qg + ((((size_t)b * p.L + l) * p.Hq + (size_t)kvh * p.g) * p.Tq + (size_t)(row_ok ? r : 0)) * D;
-    bf16x8 qf[KS];
+    bf16x8 qf[RB][KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (row_ok) v = *reinterpret_cast<const uint4 *>(qrow + ks * 16 + half * 8);
-        qf[ks] = __builtin_bit_cast(bf16x8, v);
+    for (int j = 0; j < RB; ++j) {
+        const int r = ((rg * NW + w) * RB + j) * 32 + n;
+        const uint16_t *qrow = Qg + ((((size_t)b * p.L + l) * p.Hq + (size_t)kvh * p.g) * p.Tq + (size_t)(row_ok[j] ? r : 0)) * D;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (row_ok[j]) v = *reinterpret_cast<const uint4 *>(qrow + ks * 16 + half * 8);
+            qf[j][ks] = __builtin_bit_cast(bf16x8, v);
+        }
     }
 
     // The query rows and the first split's keys have arrived before the loop starts.  Inside it a
-    // split's copy is followed by the kStores stores of the split before it, all unconditional
+    // split's copy is followed by the RB*kStores stores of the split before it, all unconditional
     // (addresses are redirected instead); memory operations complete in the order issued, so "at
     // most kStores - 2 outstanding" means this wave's part of split t has landed, without waiting
     // for the newest stores.
@@ -177,6 +189,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
         if (t + 1 < t1) copy_keys(t + 1, buf ^ 1);
 
         const int k0 = t * KR, kn = min(KR, S - k0), nkb = (kn + 31) / 32;
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
         // logits of the 32 keys of block kb against this wave's 32 rows: lane (n, half) gets row n,
         // keys 8*(v/4) + 4*half + v%4 of the block; keys the row does not see are set to -inf.  The
         // logits of all KR keys stay in registers between the maximum and the exponentials.
@@ -198,10 +212,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(ka[ks]));
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[ks], a, 0, 0, 0);
+                for (int ks = 0; ks < KS; ++ks) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[j][ks], a, 0, 0, 0);
                 const int key0 = k0 + kb * 32;
-                if (__any(key0 + 32 > row_end)) {   // some row of the wave does not see all 32 keys
-                    const int lim = row_end - key0 - 4 * half;
+                if (__any(key0 + 32 > row_end[j])) {   // some row of the wave does not see all 32 keys
+                    const int lim = row_end[j] - key0 - 4 * half;
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
                         if (8 * (v >> 2) + (v & 3) >= lim) a[v] = -INFINITY;
@@ -230,7 +244,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
                 // a block past the last key has no place in E: its zeros go to a dump area.  Rows
                 // that do not exist (and the blocks of a wave without rows) have theirs and are
                 // never read.
-                unsigned char *blk = kb < nkb ? p.E + e_block_offset(p, rbl, l, t * NKBW + kb)
+                unsigned char *blk = kb < nkb ? p.E + e_block_offset(p, rbl[j], l, t * NKBW + kb)
                                               : p.dump + (size_t)((blockIdx.x * NW + w) & (kDumpBlocks - 1)) * 2048;
                 uint4 *dst = reinterpret_cast<uint4 *>(blk + n * 64 + half * 32);
                 dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
@@ -239,9 +253,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
         }
         z += __shfl_xor(z, 32, 64);
         {   // (both half-waves hold the same values and write them to the same place)
-            const size_t o = (((size_t)rbl * 32 + n) * p.nsplit + t) * p.L + l;
+            const size_t o = (((size_t)rbl[j] * 32 + n) * p.nsplit + t) * p.L + l;
             p.rowM[o] = mx > -INFINITY ? M : kMInit;
             p.rowZ[o] = z;
+        }
         }
     }
 }
@@ -734,7 +749,7 @@ int ap_plan(const krul_shape_t *s, size_t max_bytes, APPlan *pl)
     if (Rk > INT32_MAX || (long long)s->batch * s->n_q_heads * s->n_query > INT32_MAX) return KRUL_EUNSUPPORTED;
     if (s->n_hist * (long long)s->head_dim * 4 >= (1ll << 31)) return KRUL_EUNSUPPORTED;
     const long long NRB = (Rk + 31) / 32;   // 32-row blocks per unit
-    pl->NW = NRB >= 3 ? 4 : (int)NRB;
+    pl->NW = NRB >= 6 ? 8 : (NRB >= 3 ? 4 : (int)NRB);
     pl->NRG = (int)((NRB + pl->NW - 1) / pl->NW);
     pl->NKB = (s->n_hist + 31) / 32;
     const long long total = (long long)s->batch * s->n_kv_heads * pl->NRG;
@@ -775,9 +790,10 @@ void launch_weights(const APParams &p, hipStream_t st)
 {
     const dim3 grid(p.nrg * p.L * ((p.nsplit + p.tpw - 1) / p.tpw));
     switch (p.NW) {
-    case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1>), grid, dim3(64), 0, st, p); break;
-    case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2>), grid, dim3(128), 0, st, p); break;
-    default: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4>), grid, dim3(256), 0, st, p); break;
+    case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1, 1>), grid, dim3(64), 0, st, p); break;
+    case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2, 1>), grid, dim3(128), 0, st, p); break;
+    case 4: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 1>), grid, dim3(256), 0, st, p); break;
+    default: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 2>), grid, dim3(256), 0, st, p); break;
     }
 }
 
