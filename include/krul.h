@@ -222,7 +222,7 @@ int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
  *                   in it (fp16), as the paper keeps them (Sec. 5), so its size sets how many rows one
  *                   batch holds: krul_all_pairs_workspace(shape, max_bytes) returns the bytes for the
  *                   largest batch that fits max_bytes (max_bytes 0: a default budget of 4 GiB; never
- *                   less than the bytes for the smallest batch, 128 rows of one kv head), or 0 if the
+ *                   less than the bytes for the smallest batch, up to 256 rows of one kv head), or 0 if the
  *                   shape is not supported.  Any size from the smallest batch's up is accepted by the
  *                   call; more memory means fewer, larger launches.
  * Limits: n_layers <= 128.  bf16 with head_dim 64 or 128 runs on the matrix cores; other inputs take a

@@ -8,10 +8,10 @@
 // exponentials ARE written out -- as the paper itself keeps the attention weights (Sec. 5) -- in
 // fp16, in batches of rows sized to the workspace the caller gives:
 //
-//   1. weights kernel: a workgroup of NW waves owns NW 32-row blocks of a unit (NW = 1, 2 or 4 with
-//      the rows a kv head has), one layer, and a run of key splits of 128 keys.  Per split: the keys
-//      go to one of two XOR-swizzled LDS buffers (the next split's are already in flight: through
-//      registers for NW = 4, by buffer_load ... lds for the narrow workgroups), one barrier,
+//   1. weights kernel: a workgroup owns a row group of a unit -- 1, 2, 4 or 8 32-row blocks with
+//      the rows a kv head has: up to four waves, each with one or two blocks --, one layer, and a
+//      run of key splits of 128 keys.  Per split: the keys go to one of two XOR-swizzled LDS
+//      buffers by buffer_load ... lds (the next split's are already in flight), one barrier,
 //      v_mfma_f32_32x32x16_bf16 logits of all 128 keys into registers, their maximum m (one exchange
 //      between the two half-waves: a wave owns all 128 keys of its 32 rows), e = 2^(x - m) <= 1,
 //      Z = sum e, and the fp16 store of e.  m and Z are kept per (row, layer, split).

@@ -85,7 +85,7 @@ def test_batches_of_any_size_give_the_same_bits(G):
     q, k = G.to_device(w)
     shp = kr.make_shape(q, k)
     full = kr.all_pairs_workspace_bytes(shp)
-    one = kr.all_pairs_workspace_bytes(shp, 1)            # the smallest batch: one 128-row group
+    one = kr.all_pairs_workspace_bytes(shp, 1)            # the smallest batch: one row group
     three = kr.all_pairs_workspace_bytes(shp, one * 3)    # batches that straddle kv heads
     assert one < three < full
     ref = gpu_all_pairs(q, k)
