@@ -626,6 +626,7 @@ __global__ __launch_bounds__(kThreads) void ap_final_kernel(int B, int L, int Hq
 // scan of the stably sorted list takes.  Order: key ascending (distance, or minus similarity),
 // equal keys by lower j, then lower i.
 constexpr int kSelThreads = 256;
+constexpr int kSelLdsLayers = 96;   // up to this many layers the ordering keys are kept in LDS
 
 __global__ __launch_bounds__(kSelThreads) void select_all_kernel(
     const float *__restrict__ score, int closer_is_smaller, const uint8_t *__restrict__ eligible,
@@ -635,10 +636,14 @@ __global__ __launch_bounds__(kSelThreads) void select_all_kernel(
     uint8_t *used = sm;                                                      // [L]: shared already, or not eligible
     float *bkey = reinterpret_cast<float *>(sm + ((L + 15) & ~15));          // [waves]
     int *brank = reinterpret_cast<int *>(bkey + kSelThreads / 64);           // [waves]
+    float *keys = reinterpret_cast<float *>(brank + kSelThreads / 64);       // [L*L] if L <= kSelLdsLayers
     __shared__ int chosen;
     const int b = blockIdx.x, tid = threadIdx.x;
     const float *sc = score + (size_t)b * L * L;
+    const bool in_lds = L <= kSelLdsLayers;
     for (int l = tid; l < L; l += kSelThreads) used[l] = eligible ? (eligible[(size_t)b * L + l] ? 0 : 1) : 0;
+    if (in_lds)
+        for (int e = tid; e < L * L; e += kSelThreads) keys[e] = closer_is_smaller ? sc[e] : -sc[e];
     __syncthreads();
     int cnt = 0;
     for (; cnt < n_select; ++cnt) {
@@ -647,7 +652,7 @@ __global__ __launch_bounds__(kSelThreads) void select_all_kernel(
         for (int e = tid; e < L * L; e += kSelThreads) {
             const int i = e / L, j = e % L;
             if (i <= j || used[i] || used[j]) continue;
-            const float key = closer_is_smaller ? sc[e] : -sc[e];
+            const float key = in_lds ? keys[e] : (closer_is_smaller ? sc[e] : -sc[e]);
             const int rk = j * L + i;
             if (rank == INT32_MAX || key < best || (key == best && rk < rank)) {
                 best = key;
@@ -901,7 +906,8 @@ hipError_t launch_select_all(const float *score, int closer_is_smaller, const ui
                              int n_layers, int n_select, int32_t *out_pairs, int32_t *out_count, hipStream_t st)
 {
     const size_t smem = ((n_layers + 15) & ~15) + (kSelThreads / 64) * (sizeof(float) + sizeof(int));
-    hipLaunchKernelGGL(select_all_kernel, dim3(batch), dim3(kSelThreads), smem, st, score, closer_is_smaller,
+    const size_t smem_keys = n_layers <= kSelLdsLayers ? (size_t)n_layers * n_layers * sizeof(float) : 0;
+    hipLaunchKernelGGL(select_all_kernel, dim3(batch), dim3(kSelThreads), smem + smem_keys, st, score, closer_is_smaller,
                        eligible, n_layers, n_select, out_pairs, out_count);
     return hipGetLastError();
 }
