@@ -106,7 +106,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"],
+                    help="C5 draws 22.5 GiB of inputs on the host first (minutes); give it few --steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--with-dist", action="store_true",
@@ -134,7 +135,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    w = workloads.config(args.config)
+    w = workloads.config(args.config, progress=lambda b, n: print(f"bench.py: drew conversation {b + 1} of {n}",
+                                                                    file=sys.stderr, flush=True) if args.config == "C5" else None)
     if w.dtype == "f32":
         q, k = torch.from_numpy(w.q).cuda(), torch.from_numpy(w.k).cuda()
     else:

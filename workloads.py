@@ -82,8 +82,9 @@ def _store(x: np.ndarray, dtype: str) -> np.ndarray:
 
 
 def make(name: str = "custom", *, B, L, Hq, Hkv, d, S, Tq, dtype="bf16", n_select=None,
-         rho_k=0.8, rho_q=0.95, seed=BASE_SEED, sink_frac=0.0, sink_gain=4.0) -> Workload:
-    """Draw one workload.  rho_k: scalar, or an array broadcastable to [B, L-1, Hkv]."""
+         rho_k=0.8, rho_q=0.95, seed=BASE_SEED, sink_frac=0.0, sink_gain=4.0, progress=None) -> Workload:
+    """Draw one workload.  rho_k: scalar, or an array broadcastable to [B, L-1, Hkv].
+    progress: called with (conversation index, B) after each conversation is drawn (large workloads)."""
     rho = np.broadcast_to(np.asarray(rho_k, dtype=np.float32), (B, L - 1, Hkv)).copy()
     store_t = np.float32 if dtype == "f32" else np.uint16
     q = np.empty((B, L, Hq, Tq, d), dtype=store_t)
@@ -107,12 +108,14 @@ def make(name: str = "custom", *, B, L, Hq, Hkv, d, S, Tq, dtype="bf16", n_selec
                 qc = np.float32(rho_q) * qc + cq * re_q.standard_normal((Hq, Tq, d), dtype=np.float32)
             q[b, l] = _store(qc, dtype)
             k[b, l] = _store(kc if gain is None else kc * gain, dtype)
+        if progress is not None:
+            progress(b, B)
     if n_select is None:
         n_select = max(1, L // 4)
     return Workload(name, B, L, Hq, Hkv, d, S, Tq, dtype, n_select, q, k, rho, rho_q, sinks)
 
 
-def config(name: str, *, batch=None, seed=None) -> Workload:
+def config(name: str, *, batch=None, seed=None, progress=None) -> Workload:
     """One of the five benchmark configurations C1..C5 (full size unless batch is cut)."""
     B, L, Hq, Hkv, d, S, Tq, dtype, n_select = CONFIGS[name]
     if batch is not None:
@@ -129,7 +132,7 @@ def config(name: str, *, batch=None, seed=None) -> Workload:
     if name == "C3":
         kw = dict(sink_frac=0.02, sink_gain=4.0)
     return make(name, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, dtype=dtype, n_select=n_select,
-                rho_k=rho, seed=seed, **kw)
+                rho_k=rho, seed=seed, progress=progress, **kw)
 
 
 def scaled(name: str, *, S=None, Tq=None, L=None, batch=None, seed=None) -> Workload:
