@@ -247,7 +247,7 @@ int krul_all_pairs_similarity(const krul_shape_t *shape, const void *q, const vo
  *   out_pairs  [B][n_select][2] int32          device: (j, i) of each taken pair in the order taken,
  *                                              (-1, -1) after out_count[b]
  *   out_count  [B] int32                       device
- * Limits: 2 <= n_layers <= 4096, 0 <= n_select <= n_layers/2.
+ * Limits: 2 <= n_layers <= 1024, 0 <= n_select <= n_layers/2.
  */
 int krul_select_pairs_all(const float *score, int32_t closer_is_smaller, const uint8_t *eligible,
                           int32_t batch, int32_t n_layers, int32_t n_select,

@@ -282,7 +282,7 @@ int krul_select_pairs_all(const float *score, int32_t closer_is_smaller, const u
         (n_select > 0 && !out_pairs))
         return KRUL_EINVAL;
     if (((uintptr_t)score | (uintptr_t)out_pairs | (uintptr_t)out_count) & 3) return KRUL_EINVAL;
-    if (n_layers > 4096) return KRUL_EUNSUPPORTED;
+    if (n_layers > 1024) return KRUL_EUNSUPPORTED;   // (n_select rounds over n_layers^2 entries)
     const hipError_t e = launch_select_all(score, closer_is_smaller, eligible, batch, n_layers, n_select, out_pairs,
                                            out_count, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
