@@ -60,6 +60,11 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
         // the wide tile's workgroups are resident one per CU: aim for one round of them
         const long long target = y.variant == kMfmaWide ? kTargetWorkgroups / 2 : kTargetWorkgroups;
         long long want = (target + units - 1) / units;
+        // The narrow tiles are bound by the stream of keys: there a split of several tiles, which
+        // parks its running records in memory between tiles, costs a quarter of the bandwidth (a decode
+        // step over 131072 tokens: 57 % of 8 TB/s against 74 % with one tile per split), and the
+        // partial records stay below 1 % of the key bytes.  So: one tile per split, up to 1024 splits.
+        if (y.variant != kMfmaWide && want < 1024) want = 1024;
         if (want < 1 || (s->flags & KRUL_FLAG_SINGLE_SPLIT)) want = 1;
         long long nsplit = want < tiles ? want : tiles;
         const long long tps = (tiles + nsplit - 1) / nsplit;
