@@ -7,7 +7,7 @@ kernel, no helper.  See the header of ``krul_oracle.c`` for what each function
 computes and which passage of the paper (Sec. 2.1, Sec. 4.2 / Alg. 1, Sec. 5,
 Sec. 7) it follows.
 
-Inputs are numpy arrays: float32, or uint16 holding bf16 bit patterns.
+Inputs are numpy arrays: float32, float16, or uint16 holding bf16 bit patterns.
 """
 from __future__ import annotations
 
@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "krul_oracle.c")
 _LIB = os.path.join(_HERE, "libkrul_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 
 class _Shape(ctypes.Structure):
@@ -68,8 +68,10 @@ def _prep(q: np.ndarray, k: np.ndarray, scale, causal=False):
         dt = F32
     elif q.dtype == np.uint16:
         dt = BF16
+    elif q.dtype == np.float16:
+        dt = F16
     else:
-        raise ValueError("dtype must be float32 or uint16 (bf16 bits)")
+        raise ValueError("dtype must be float32, float16 or uint16 (bf16 bits)")
     B, L, Hq, Tq, d = q.shape
     B2, L2, Hkv, S, d2 = k.shape
     if (B, L, d) != (B2, L2, d2):

@@ -46,11 +46,11 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 typedef struct {
     int32_t batch, n_layers, n_q_heads, n_kv_heads, head_dim, n_hist, n_query;
-    int32_t dtype;   /* ORACLE_F32 or ORACLE_BF16 (raw 16-bit patterns) */
+    int32_t dtype;   /* ORACLE_F32, ORACLE_BF16 or ORACLE_F16 (raw 16-bit patterns: bfloat16, IEEE binary16) */
     double scale;    /* <= 0 means 1/sqrt(head_dim)  (Sec. 2.1) */
     int32_t causal;  /* 0: every query row sees all n_hist keys.  1: the n_query rows are the last
                         n_query tokens of the n_hist-token sequence and row t sees the keys up to
@@ -63,6 +63,18 @@ static double elem(const void *p, int dtype, size_t i)
 {
     if (dtype == ORACLE_F32)
         return (double)((const float *)p)[i];
+    if (dtype == ORACLE_F16) {   /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+        const uint16_t h = ((const uint16_t *)p)[i];
+        const int sign = h >> 15, ex = (h >> 10) & 31, frac = h & 1023;
+        double v;
+        if (ex == 0)
+            v = ldexp((double)frac, -24);                 /* zero and subnormals: frac * 2^-24 */
+        else if (ex == 31)
+            v = frac ? NAN : INFINITY;
+        else
+            v = ldexp((double)(1024 + frac), ex - 25);    /* (1 + frac/1024) * 2^(ex-15) */
+        return sign ? -v : v;
+    }
     uint32_t bits = (uint32_t)((const uint16_t *)p)[i] << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
@@ -154,7 +166,7 @@ static int shape_ok(const oracle_shape_t *s)
 {
     return s && s->batch > 0 && s->n_layers >= 2 && s->n_q_heads > 0 && s->n_kv_heads > 0 &&
            s->n_q_heads % s->n_kv_heads == 0 && s->head_dim > 0 && s->n_hist > 0 &&
-           s->n_query > 0 && (s->dtype == ORACLE_F32 || s->dtype == ORACLE_BF16) &&
+           s->n_query > 0 && (s->dtype == ORACLE_F32 || s->dtype == ORACLE_BF16 || s->dtype == ORACLE_F16) &&
            (s->causal == 0 || (s->causal == 1 && s->n_hist >= s->n_query));
 }
 

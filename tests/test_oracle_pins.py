@@ -84,6 +84,46 @@ def test_bf16_bits_are_widened_exactly(oracle):
     assert np.max(np.abs(workloads.bf16_bits_to_f32(qb) / q - 1)) < 2.0 ** -8
 
 
+def test_f16_bits_are_widened_exactly(oracle):
+    """IEEE binary16 inputs: the same numbers as their float32 images (numpy's conversion), over
+    normal, subnormal, tiny and large finite values."""
+    rng = np.random.default_rng(4)
+    q, k = rand_qk(rng, 1, 3, 4, 2, 3, 9, 8)
+    qh, kh = q.astype(np.float16), k.astype(np.float16)
+    # plant special patterns: subnormals, the smallest and largest normals, signed zeros
+    special = np.array([0x0001, 0x03FF, 0x0400, 0x7BFF, 0x8001, 0x8000, 0x0000, 0x3555, 0xFBFF, 0x0200],
+                       dtype=np.uint16).view(np.float16) * np.float16(1.0)
+    kh.reshape(-1)[:special.size] = special * np.float16(1e-3)     # keep the logits finite ...
+    kh.reshape(-1)[special.size:2 * special.size] = special.view(np.uint16).view(np.float16)
+    kh = np.where(np.abs(kh.astype(np.float32)) > 100, np.float16(0.5), kh)   # ... and drop the huge ones
+    kh.reshape(-1)[40] = np.uint16(0x0001).view(np.float16)          # a subnormal stays
+    o_h = oracle.pair_similarity(qh, kh)
+    o_f = oracle.pair_similarity(qh.astype(np.float32), kh.astype(np.float32))
+    for key in o_h:
+        np.testing.assert_array_equal(o_h[key], o_f[key])
+    assert np.max(np.abs(qh.astype(np.float32) - q)) > 1e-5          # rounding really happened
+    # every bit pattern, through a one-key problem whose single logit is q * k with q = 1:
+    # distance of the two layers' rows is 0 (one key), so use the scale to read values back instead:
+    # softmax over two keys (k, 0) with q = 1, d = 1: p0 = 1 / (1 + exp(-k * scale))
+    pats = np.arange(0, 0x7C00, 37, dtype=np.uint16)                 # finite non-negative patterns
+    vals = pats.view(np.float16)
+    kk = np.zeros((1, 2, 1, 2, 1), dtype=np.float16)
+    qq = np.ones((1, 2, 1, 1, 1), dtype=np.float16)
+    for v in vals[::16]:
+        kk[0, 0, 0, 0, 0] = v
+        kk[0, 1, 0, 0, 0] = v
+        a = oracle.pair_similarity(qq, kk, scale=1e-3)
+        b = oracle.pair_similarity(qq.astype(np.float32), kk.astype(np.float32), scale=1e-3)
+        assert a["head_dist"][0, 0, 0] == b["head_dist"][0, 0, 0] == 0.0
+        # and against a second layer with k = 0 the distance is a strictly monotone function of the value
+        kk[0, 1, 0, 0, 0] = 0
+        a = oracle.pair_similarity(qq, kk, scale=1e-3)
+        b = oracle.pair_similarity(qq.astype(np.float32), kk.astype(np.float32), scale=1e-3)
+        assert a["head_dist"][0, 0, 0] == b["head_dist"][0, 0, 0]
+        p0 = 1.0 / (1.0 + np.exp(-float(v) * 1e-3))
+        np.testing.assert_allclose(a["head_dist"][0, 0, 0], np.sqrt(2) * abs(p0 - 0.5), rtol=1e-9, atol=1e-15)
+
+
 def test_identical_layers_score_one(oracle):
     rng = np.random.default_rng(4)
     q, k = rand_qk(rng, 2, 2, 4, 2, 5, 40, 8)

@@ -49,9 +49,9 @@ class Workload:
     d: int
     S: int
     Tq: int
-    dtype: str            # "f32" or "bf16"
+    dtype: str            # "f32", "f16" or "bf16"
     n_select: int
-    q: np.ndarray         # float32, or uint16 bf16 bits
+    q: np.ndarray         # float32, float16, or uint16 bf16 bits
     k: np.ndarray
     rho_k: np.ndarray     # [B, L-1, Hkv] correlation used for each pair and kv head
     rho_q: float
@@ -78,7 +78,9 @@ def _rng(seed: int, stream: int) -> np.random.Generator:
 
 
 def _store(x: np.ndarray, dtype: str) -> np.ndarray:
-    return x.astype(np.float32, copy=True) if dtype == "f32" else f32_to_bf16_bits(x)
+    if dtype == "f32":
+        return x.astype(np.float32, copy=True)
+    return x.astype(np.float16) if dtype == "f16" else f32_to_bf16_bits(x)
 
 
 def make(name: str = "custom", *, B, L, Hq, Hkv, d, S, Tq, dtype="bf16", n_select=None,
@@ -86,7 +88,7 @@ def make(name: str = "custom", *, B, L, Hq, Hkv, d, S, Tq, dtype="bf16", n_selec
     """Draw one workload.  rho_k: scalar, or an array broadcastable to [B, L-1, Hkv].
     progress: called with (conversation index, B) after each conversation is drawn (large workloads)."""
     rho = np.broadcast_to(np.asarray(rho_k, dtype=np.float32), (B, L - 1, Hkv)).copy()
-    store_t = np.float32 if dtype == "f32" else np.uint16
+    store_t = {"f32": np.float32, "f16": np.float16}.get(dtype, np.uint16)
     q = np.empty((B, L, Hq, Tq, d), dtype=store_t)
     k = np.empty((B, L, Hkv, S, d), dtype=store_t)
     rq, rk, re_q, re_k = _rng(seed, 1), _rng(seed, 2), _rng(seed, 3), _rng(seed, 4)
