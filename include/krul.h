@@ -34,7 +34,7 @@ typedef enum {
     KRUL_EUNSUPPORTED = -5  /* valid request with no kernel (head_dim, n_layers limits) */
 } krul_status_t;
 
-typedef enum { KRUL_F32 = 0, KRUL_BF16 = 1 } krul_dtype_t;
+typedef enum { KRUL_F32 = 0, KRUL_BF16 = 1, KRUL_F16 = 2 /* IEEE binary16 */ } krul_dtype_t;
 
 /* flags of krul_shape_t */
 enum {
@@ -61,8 +61,8 @@ typedef struct {
     int32_t n_q_heads;    /* Hq  query heads                                       */
     int32_t n_kv_heads;   /* Hkv key heads, divides Hq; query head h reads kv head
                                  h / (Hq/Hkv)                                      */
-    int32_t head_dim;     /* d   64 or 128 for bf16; multiple of 8, <= 256 for the
-                                 portable kernel                                   */
+    int32_t head_dim;     /* d   64 or 128 for the matrix-core kernels (bf16, f16);
+                                 any multiple of 8 up to 256 for the portable one  */
     int32_t n_hist;       /* S   history keys per layer (every query row sees all) */
     int32_t n_query;      /* Tq  query rows (tokens) per head                      */
     int32_t dtype;        /* krul_dtype_t of q and k                               */
@@ -138,7 +138,7 @@ int krul_pair_similarity_ir(const krul_shape_t *shape, const void *q, const void
  *               elements between conversations, kv heads and keys inside a layer: key (b, h, j) starts at
  *               k_layers[l] + b*k_stride_b + h*k_stride_h + j*k_stride_s; its head_dim elements are
  *               contiguous.  All > 0 and multiples of 8 elements (k_stride_b is ignored for batch 1),
- *               k_stride_s >= head_dim (else KRUL_EINVAL); for bf16 with head_dim 64 or 128, k_stride_s must
+ *               k_stride_s >= head_dim (else KRUL_EINVAL); for bf16 / f16 with head_dim 64 or 128, k_stride_s must
  *               be a multiple of head_dim and n_hist * k_stride_s * 2 bytes < 2 GiB (else KRUL_EUNSUPPORTED).
  * The caller guarantees that every addressed key lies inside its layer's allocation.  Everything else
  * is as for krul_pair_similarity (same workspace size).
@@ -225,7 +225,7 @@ int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
  *                   less than the bytes for the smallest batch, up to 256 rows of one kv head), or 0 if the
  *                   shape is not supported.  Any size from the smallest batch's up is accepted by the
  *                   call; more memory means fewer, larger launches.
- * Limits: n_layers <= 128.  bf16 with head_dim 64 or 128 runs on the matrix cores; other inputs take a
+ * Limits: n_layers <= 128.  bf16 or f16 with head_dim 64 or 128 runs on the matrix cores; other inputs take a
  * portable, slow kernel.  Exponentials are rounded to fp16 (2^-11 relative) before the products.
  * Results are deterministic.  Errors as for krul_pair_similarity.
  */

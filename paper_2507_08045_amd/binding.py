@@ -18,7 +18,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libkrul.so")
 
 KRUL_OK, KRUL_EINVAL, KRUL_EDTYPE, KRUL_EWORKSPACE, KRUL_ELAUNCH, KRUL_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
-KRUL_F32, KRUL_BF16 = 0, 1
+KRUL_F32, KRUL_BF16, KRUL_F16 = 0, 1, 2
+_DTYPES = {torch.float32: KRUL_F32, torch.bfloat16: KRUL_BF16, torch.float16: KRUL_F16}
 KRUL_FLAG_CAUSAL = 1 << 0
 KRUL_FLAG_GENERIC_KERNEL = 1 << 8
 KRUL_FLAG_SINGLE_SPLIT = 1 << 9
@@ -104,13 +105,13 @@ def n_select_from_ratio(n_layers: int, r_l: float) -> int:
 def make_shape(q: torch.Tensor, k: torch.Tensor, scale: float = 0.0, flags: int = 0) -> KrulShape:
     if q.dim() != 5 or k.dim() != 5:
         raise ValueError("q must be [B,L,Hq,Tq,d] and k [B,L,Hkv,S,d]")
-    if q.dtype != k.dtype or q.dtype not in (torch.float32, torch.bfloat16):
-        raise ValueError("q and k must both be float32 or both bfloat16")
+    if q.dtype != k.dtype or q.dtype not in _DTYPES:
+        raise ValueError("q and k must both be float32, both bfloat16 or both float16")
     B, L, Hq, Tq, d = q.shape
     B2, L2, Hkv, S, d2 = k.shape
     if (B, L, d) != (B2, L2, d2):
         raise ValueError("q and k disagree on batch, layers or head_dim")
-    dt = KRUL_F32 if q.dtype == torch.float32 else KRUL_BF16
+    dt = _DTYPES[q.dtype]
     return KrulShape(B, L, Hq, Hkv, d, S, Tq, dt, float(scale), int(flags))
 
 
@@ -191,12 +192,12 @@ def pair_similarity_strided(q: torch.Tensor, k_layers, *, scale: float = 0.0, fl
                            for t in k_layers):
         raise ValueError("q must be [B,L,Hq,Tq,d] and every k_layers[l] a [B,Hkv,S,d] view of one shape, "
                          "one set of strides and q's dtype")
-    if k0.stride(3) != 1 or q.dtype not in (torch.float32, torch.bfloat16):
-        raise ValueError("head_dim must be contiguous; dtype float32 or bfloat16")
+    if k0.stride(3) != 1 or q.dtype not in _DTYPES:
+        raise ValueError("head_dim must be contiguous; dtype float32, bfloat16 or float16")
     B, L, Hq, Tq, d = q.shape
     if len(k_layers) != L or k0.shape[0] != B or k0.shape[3] != d:
         raise ValueError("q and k disagree on batch, layers or head_dim")
-    shp = KrulShape(B, L, Hq, k0.shape[1], d, k0.shape[2], Tq, KRUL_F32 if q.dtype == torch.float32 else KRUL_BF16,
+    shp = KrulShape(B, L, Hq, k0.shape[1], d, k0.shape[2], Tq, _DTYPES[q.dtype],
                     float(scale), int(flags))
     if k_table is None:
         k_table = torch.tensor([t.data_ptr() for t in k_layers], dtype=torch.int64).to(q.device)

@@ -101,7 +101,7 @@ __device__ inline uint32_t pack_f16(float a, float b)
 // 1. weights kernel (bf16, head_dim 64 or 128)
 // NW waves, each with RB 32-row blocks (taken one after the other against the same keys in LDS): a
 // row group is NW*RB blocks.
-template <int D, int NW, int RB>
+template <int D, int NW, int RB, bool F16>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kernel(APParams p)
 {
     constexpr int KS = D / 16, ROWB = D * 2, KR = kKeysPerSplit, NKBW = KR / 32;
@@ -212,7 +212,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(ka[ks]));
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[j][ks], a, 0, 0, 0);
+                for (int ks = 0; ks < KS; ++ks) {
+                    if constexpr (F16)   // IEEE binary16 inputs: same layout, same rate
+                        a = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, ka[ks]),
+                                                                   __builtin_bit_cast(f16x8, qf[j][ks]), a, 0, 0, 0);
+                    else
+                        a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[j][ks], a, 0, 0, 0);
+                }
                 const int key0 = k0 + kb * 32;
                 if (__any(key0 + 32 > row_end[j])) {   // some row of the wave does not see all 32 keys
                     const int lim = row_end[j] - key0 - 4 * half;
@@ -269,6 +275,8 @@ template <>
 __device__ inline float load_f32<float>(const float *ptr, size_t i) { return ptr[i]; }
 template <>
 __device__ inline float load_f32<uint16_t>(const uint16_t *ptr, size_t i) { return __uint_as_float((uint32_t)ptr[i] << 16); }
+template <>
+__device__ inline float load_f32<_Float16>(const _Float16 *ptr, size_t i) { return (float)ptr[i]; }
 
 template <typename T>
 __global__ __launch_bounds__(64) void ap_weights_generic_kernel(APParams p)
@@ -760,7 +768,7 @@ int ap_plan(const krul_shape_t *s, size_t max_bytes, APPlan *pl)
     const long long total = (long long)s->batch * s->n_kv_heads * pl->NRG;
     if (total * pl->NW * 32 > INT32_MAX / 4) return KRUL_EUNSUPPORTED;
     pl->total_rg = (int)total;
-    pl->mfma = s->dtype == KRUL_BF16 && (s->head_dim == 64 || s->head_dim == 128) &&
+    pl->mfma = (s->dtype == KRUL_BF16 || s->dtype == KRUL_F16) && (s->head_dim == 64 || s->head_dim == 128) &&
                !(s->flags & KRUL_FLAG_GENERIC_KERNEL);
     // key splits of the weights kernel: one per kKeysPerSplit keys (the portable kernel does not split)
     if (pl->mfma) {
@@ -790,15 +798,15 @@ int ap_plan(const krul_shape_t *s, size_t max_bytes, APPlan *pl)
     return KRUL_OK;
 }
 
-template <int D>
+template <int D, bool F16>
 void launch_weights(const APParams &p, hipStream_t st)
 {
     const dim3 grid(p.nrg * p.L * ((p.nsplit + p.tpw - 1) / p.tpw));
     switch (p.NW) {
-    case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1, 1>), grid, dim3(64), 0, st, p); break;
-    case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2, 1>), grid, dim3(128), 0, st, p); break;
-    case 4: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 1>), grid, dim3(256), 0, st, p); break;
-    default: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 2>), grid, dim3(256), 0, st, p); break;
+    case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1, 1, F16>), grid, dim3(64), 0, st, p); break;
+    case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2, 1, F16>), grid, dim3(128), 0, st, p); break;
+    case 4: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 1, F16>), grid, dim3(256), 0, st, p); break;
+    default: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 2, F16>), grid, dim3(256), 0, st, p); break;
     }
 }
 
@@ -874,12 +882,15 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
         p.nrg = pl.nrg_batch < pl.total_rg - g0 ? pl.nrg_batch : pl.total_rg - g0;
         const int rblocks = p.nrg * p.NW, rows = rblocks * 32;
         if (pl.mfma) {
+            const bool f16 = s->dtype == KRUL_F16;
             if (p.d == 128)
-                launch_weights<128>(p, st);
+                f16 ? launch_weights<128, true>(p, st) : launch_weights<128, false>(p, st);
             else
-                launch_weights<64>(p, st);
+                f16 ? launch_weights<64, true>(p, st) : launch_weights<64, false>(p, st);
         } else if (s->dtype == KRUL_F32) {
             hipLaunchKernelGGL(ap_weights_generic_kernel<float>, dim3(rows * L), dim3(64), p.d * sizeof(float), st, p);
+        } else if (s->dtype == KRUL_F16) {
+            hipLaunchKernelGGL(ap_weights_generic_kernel<_Float16>, dim3(rows * L), dim3(64), p.d * sizeof(float), st, p);
         } else {
             hipLaunchKernelGGL(ap_weights_generic_kernel<uint16_t>, dim3(rows * L), dim3(64), p.d * sizeof(float), st, p);
         }

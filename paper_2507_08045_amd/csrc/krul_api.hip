@@ -17,7 +17,7 @@ size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 int check_shape(const krul_shape_t *s)
 {
     if (!s) return KRUL_EINVAL;
-    if (s->dtype != KRUL_F32 && s->dtype != KRUL_BF16) return KRUL_EDTYPE;
+    if (s->dtype != KRUL_F32 && s->dtype != KRUL_BF16 && s->dtype != KRUL_F16) return KRUL_EDTYPE;
     if (s->batch <= 0 || s->n_layers < 2 || s->n_q_heads <= 0 || s->n_kv_heads <= 0 ||
         s->head_dim <= 0 || s->n_hist <= 0 || s->n_query <= 0)
         return KRUL_EINVAL;
@@ -45,7 +45,7 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
     y.n_layers = (int)L;
     y.rows_per_unit = (int)Rk;
 
-    const bool mfma = s->dtype == KRUL_BF16 && (s->head_dim == 64 || s->head_dim == 128) &&
+    const bool mfma = (s->dtype == KRUL_BF16 || s->dtype == KRUL_F16) && (s->head_dim == 64 || s->head_dim == 128) &&
                       !(s->flags & KRUL_FLAG_GENERIC_KERNEL);
     long long n_wg, records, spill_records = 0;
     if (mfma) {
@@ -168,6 +168,7 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     p.want_dist = pair_dist != nullptr || ir;   // the test needs Z as well
     p.want_ir = ir;
     p.causal = (shape->flags & KRUL_FLAG_CAUSAL) != 0;
+    p.f16 = shape->dtype == KRUL_F16;
     // T_initial = T[:10% s], T_recent = T[90% s:] (Sec. 4.2): keys [0, floor(0.1 S)) and [floor(0.9 S), S)
     p.ir_init_end = (int)floor(0.1 * (double)p.S);
     p.ir_recent_begin = (int)floor(0.9 * (double)p.S);

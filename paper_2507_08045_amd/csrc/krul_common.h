@@ -77,6 +77,7 @@ struct SimParams {
     // [0, ir_init_end) and [ir_recent_begin, S), one float per record, laid out like state / spill
     int want_ir;
     int causal;   // row t sees keys j <= S - Tq + t (KRUL_FLAG_CAUSAL)
+    int f16;      // the 16-bit inputs are IEEE binary16, not bfloat16 (MFMA variants)
     // Where the keys are (elements of the storage type): layer l starts at k_tab[l] if k_tab is
     // set (a device array of device pointers), else at k + l * k_stride_l; inside a layer the key
     // (b, kv head, j) starts at b * k_stride_b + kvh * k_stride_h + j * k_stride_s, head_dim contiguous.

@@ -1,4 +1,5 @@
-// Portable similarity kernel (fp32 VALU arithmetic, any head_dim multiple of 8).
+// Portable similarity kernel (fp32 VALU arithmetic; float32, bfloat16 or binary16 inputs; any head_dim
+// multiple of 8).
 //
 // One wavefront owns one query row (conversation, query head, token) and one key
 // split.  It walks its keys 64 at a time (one key per lane) and, for each group of
@@ -63,12 +64,28 @@ __device__ inline float dot_row<uint16_t>(const float *qs, const uint16_t *krow,
     return acc;
 }
 
+template <>
+__device__ inline float dot_row<_Float16>(const float *qs, const _Float16 *krow, int d)
+{
+    float acc = 0.f;
+    const uint4 *kp = reinterpret_cast<const uint4 *>(krow);
+    for (int i = 0; i < d / 8; ++i) {
+        const uint4 kv = kp[i];
+        const _Float16 *h = reinterpret_cast<const _Float16 *>(&kv);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc = fmaf(qs[8 * i + j], (float)h[j], acc);
+    }
+    return acc;
+}
+
 template <typename T>
 __device__ inline float load_as_f32(const T *p, size_t i);
 template <>
 __device__ inline float load_as_f32<float>(const float *p, size_t i) { return p[i]; }
 template <>
 __device__ inline float load_as_f32<uint16_t>(const uint16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+template <>
+__device__ inline float load_as_f32<_Float16>(const _Float16 *p, size_t i) { return (float)p[i]; }
 
 template <typename T>
 __global__ __launch_bounds__(64) void sim_generic_kernel(SimParams p)
@@ -149,6 +166,8 @@ hipError_t launch_sim_generic(const SimParams &p, int dtype, int n_workgroups, h
     const size_t smem = sizeof(float) * (5 * (size_t)p.L + p.d);
     if (dtype == KRUL_F32)
         hipLaunchKernelGGL(sim_generic_kernel<float>, dim3(n_workgroups), dim3(64), smem, st, p);
+    else if (dtype == KRUL_F16)
+        hipLaunchKernelGGL(sim_generic_kernel<_Float16>, dim3(n_workgroups), dim3(64), smem, st, p);
     else
         hipLaunchKernelGGL(sim_generic_kernel<uint16_t>, dim3(n_workgroups), dim3(64), smem, st, p);
     return hipGetLastError();

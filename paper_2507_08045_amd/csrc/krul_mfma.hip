@@ -1,4 +1,4 @@
-// bf16 MFMA similarity kernel for gfx950 (CDNA4).
+// 16-bit (bfloat16 or IEEE binary16) MFMA similarity kernel for gfx950 (CDNA4).
 //
 // Work decomposition.  A "unit" is one (conversation, kv head): its (Hq/Hkv)*Tq
 // query rows all read the same keys.  A workgroup (8 wavefronts, WR x WK) owns R_WG rows
@@ -44,7 +44,8 @@
 namespace krul {
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;   // eight 16-bit elements (bfloat16, or binary16 bits)
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr float kLazy = 16.0f;
@@ -106,7 +107,18 @@ __device__ inline const uint16_t *uniform_ptr(const uint16_t *ptr)
                               (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a));
 }
 
-template <class C, int MODE, bool SK>
+// One 32x32x16 step on eight 16-bit elements per lane and operand: bfloat16, or (F16) IEEE binary16 --
+// same operand layout, same rate, so the kernel is the same for both.
+template <bool F16>
+__device__ inline f32x16 mfma_16bit(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+template <class C, int MODE, bool SK, bool F16>
 __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 {
     constexpr int D = C::D, WK = C::WK, KBW = C::KBW, NC = C::NC, KS = C::KS;
@@ -250,8 +262,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         for (int v = 0; v < 16; ++v) a[v] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                *reinterpret_cast<const bf16x8 *>(kbp + (ka_base ^ (ks << 5))), qf[ks], a, 0, 0, 0);
+            a = mfma_16bit<F16>(*reinterpret_cast<const bf16x8 *>(kbp + (ka_base ^ (ks << 5))), qf[ks], a);
         return a;
     };
 
@@ -433,7 +444,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                         constexpr int VPK = 16 / KS;
 #pragma unroll
                         for (int ks = 0; ks < KS; ++ks) {
-                            nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], qf[ks], nx, 0, 0, 0);
+                            nx = mfma_16bit<F16>(aop[ks], qf[ks], nx);
                             asm volatile("" : "+v"(nx));
 #pragma unroll
                             for (int v = ks * VPK; v < (ks + 1) * VPK; ++v) {
@@ -540,22 +551,28 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     }
 }
 
-template <class C>
-hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
+template <class C, bool F16>
+hipError_t launch_cfg_t(const SimParams &p, int n_workgroups, hipStream_t st)
 {
     const dim3 grid(n_workgroups), block(C::THREADS);
     if (p.k_tab) {   // keys in per-layer allocations, with strides (never with the Initial-Recent test)
         if (p.want_dist)
-            hipLaunchKernelGGL((sim_mfma_kernel<C, 1, true>), grid, block, 0, st, p);
+            hipLaunchKernelGGL((sim_mfma_kernel<C, 1, true, F16>), grid, block, 0, st, p);
         else
-            hipLaunchKernelGGL((sim_mfma_kernel<C, 0, true>), grid, block, 0, st, p);
+            hipLaunchKernelGGL((sim_mfma_kernel<C, 0, true, F16>), grid, block, 0, st, p);
     } else if (p.want_ir)
-        hipLaunchKernelGGL((sim_mfma_kernel<C, 2, false>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 2, false, F16>), grid, block, 0, st, p);
     else if (p.want_dist)
-        hipLaunchKernelGGL((sim_mfma_kernel<C, 1, false>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 1, false, F16>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((sim_mfma_kernel<C, 0, false>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 0, false, F16>), grid, block, 0, st, p);
     return hipGetLastError();
+}
+
+template <class C>
+hipError_t launch_cfg(const SimParams &p, int n_workgroups, hipStream_t st)
+{
+    return p.f16 ? launch_cfg_t<C, true>(p, n_workgroups, st) : launch_cfg_t<C, false>(p, n_workgroups, st);
 }
 
 }  // namespace

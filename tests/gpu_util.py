@@ -10,7 +10,7 @@ TOL = 2e-3   # absolute tolerance on similarities (cosine and distance), from th
 
 
 def to_device(w: workloads.Workload):
-    if w.dtype == "f32":
+    if w.dtype in ("f32", "f16"):
         q = torch.from_numpy(w.q).cuda()
         k = torch.from_numpy(w.k).cuda()
     else:
@@ -20,7 +20,7 @@ def to_device(w: workloads.Workload):
 
 
 def arrays_to_device(q: np.ndarray, k: np.ndarray):
-    if q.dtype == np.float32:
+    if q.dtype in (np.float32, np.float16):
         return torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda()
     return (torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16),
             torch.from_numpy(k.view(np.int16)).cuda().view(torch.bfloat16))

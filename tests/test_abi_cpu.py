@@ -65,7 +65,7 @@ def shape(kr, B=1, L=4, Hq=4, Hkv=2, d=128, S=256, Tq=8, dtype=1, scale=0.0, fla
 
 
 def test_workspace_query(kr):
-    for cfg in [dict(), dict(dtype=0, d=64), dict(S=100000, Tq=1), dict(L=80, Hq=64, Hkv=8, Tq=256, S=16384, B=8)]:
+    for cfg in [dict(), dict(dtype=0, d=64), dict(dtype=2), dict(dtype=2, d=72), dict(S=100000, Tq=1), dict(L=80, Hq=64, Hkv=8, Tq=256, S=16384, B=8)]:
         n = kr.workspace_bytes(shape(kr, **cfg))
         assert n > 0 and n % 256 == 0
     # the five benchmark configurations are all supported
