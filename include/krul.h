@@ -152,6 +152,37 @@ int krul_pair_similarity_strided(const krul_shape_t *shape, const void *q, const
                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * krul_pair_similarity on keys kept in a paged cache (the KV caches of Sec. 2.1 as paged-attention
+ * engines keep them): every layer owns a pool of fixed-size pages, a conversation's keys are spread over
+ * pages named by its row of a block table (the same row for every layer), and are scored where they are.
+ *
+ *   k_layers     DEVICE array (8-byte aligned) of n_layers device pointers to the layers' pools, 16-byte aligned
+ *   block_table  DEVICE int32 [batch][max_blocks]: page of keys [i*block_size, (i+1)*block_size) of conversation b
+ *                at block_table[b][i]; entries from ceil(n_hist / block_size) on are not read
+ *   block_size   keys per page: a power of two, >= 8
+ *   max_blocks   row length of block_table, >= ceil(n_hist / block_size)
+ *   k_stride_block, k_stride_h, k_stride_s
+ *                elements between pages, kv heads and the keys of a page: key j of conversation b, kv head h starts
+ *                at k_layers[l] + block_table[b][j / block_size]*k_stride_block + h*k_stride_h
+ *                + (j % block_size)*k_stride_s; head_dim contiguous.  All > 0, multiples of 8, k_stride_s >=
+ *                head_dim (else KRUL_EINVAL); for bf16 / f16 with head_dim 64 or 128, k_stride_s must be a multiple
+ *                of head_dim below 2^27 (else KRUL_EUNSUPPORTED).  E.g. a [num_blocks][block_size][Hkv][d] pool:
+ *                (block_size*Hkv*d, d, Hkv*d).
+ * Tables and pools are read by the kernels: they must stay valid and unchanged until the call's work on the
+ * stream has finished; the caller guarantees that every page index lies inside its pool.  Everything else is as
+ * for krul_pair_similarity (same workspace size; KRUL_FLAG_CAUSAL is honoured).
+ */
+typedef struct {
+    const void *const *k_layers;
+    const int32_t *block_table;
+    int32_t block_size, max_blocks;
+    int64_t k_stride_block, k_stride_h, k_stride_s;
+} krul_k_pages_t;
+int krul_pair_similarity_paged(const krul_shape_t *shape, const void *q, const krul_k_pages_t *k_pages,
+                               float *pair_score, float *head_score, float *pair_dist,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Token-wise accumulation over several calls (Sec. 5 and Sec. 7: the similarities of the tokens of
  * the prefill and of every decode step are added up).  krul_pair_similarity_accumulate adds, for every
  * (conversation, pair, query head), the SUM over this call's n_query rows of the row cosine to

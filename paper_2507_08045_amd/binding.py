@@ -39,6 +39,12 @@ class KrulKLayout(ctypes.Structure):
                 ("k_stride_s", ctypes.c_int64)]
 
 
+class KrulKPages(ctypes.Structure):
+    _fields_ = [("k_layers", ctypes.c_void_p), ("block_table", ctypes.c_void_p), ("block_size", ctypes.c_int32),
+                ("max_blocks", ctypes.c_int32), ("k_stride_block", ctypes.c_int64), ("k_stride_h", ctypes.c_int64),
+                ("k_stride_s", ctypes.c_int64)]
+
+
 class KrulError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
@@ -72,6 +78,9 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_strided.restype = ctypes.c_int
         L.krul_pair_similarity_strided.argtypes = [ctypes.POINTER(KrulShape), vp, ctypes.POINTER(KrulKLayout), vp, vp,
                                                    vp, vp, sz, vp]
+        L.krul_pair_similarity_paged.restype = ctypes.c_int
+        L.krul_pair_similarity_paged.argtypes = [ctypes.POINTER(KrulShape), vp, ctypes.POINTER(KrulKPages), vp, vp,
+                                                 vp, vp, sz, vp]
         L.krul_pair_similarity_accumulate.restype = ctypes.c_int
         L.krul_pair_similarity_accumulate.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, sz, vp]
         L.krul_pair_scores_from_sums.restype = ctypes.c_int
@@ -212,6 +221,46 @@ def pair_similarity_strided(q: torch.Tensor, k_layers, *, scale: float = 0.0, fl
                                             _dev_ptr(hs), _dev_ptr(pd), _dev_ptr(workspace),
                                             workspace.numel() if workspace is not None else 0,
                                             ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace, "k_table": k_table}
+
+
+def pair_similarity_paged(q: torch.Tensor, pools, block_table: torch.Tensor, n_hist: int, *, scale: float = 0.0,
+                          flags: int = 0, want_head_score: bool = True, want_pair_dist: bool = True,
+                          workspace: torch.Tensor | None = None, k_table: torch.Tensor | None = None) -> dict:
+    """krul_pair_similarity_paged on the current stream.  pools: one GPU tensor per layer indexed
+    [page, key in page, kv head, d] with any strides over the first three axes (the same for every layer) and
+    contiguous head_dim; block_table: int32 GPU tensor [B, max_blocks]; n_hist: keys per conversation."""
+    if not q.is_cuda or not all(t.is_cuda for t in pools) or not block_table.is_cuda:
+        raise ValueError("q, the pools and the block table must be GPU tensors (this library has no CPU path)")
+    p0 = pools[0]
+    if q.dim() != 5 or not q.is_contiguous() or any(t.dim() != 4 or t.stride() != p0.stride() or t.dtype != q.dtype
+                                                     for t in pools):
+        raise ValueError("q must be contiguous [B,L,Hq,Tq,d]; every pool a [pages, block, Hkv, d] tensor with one "
+                         "set of strides and q's dtype")
+    if p0.stride(3) != 1 or q.dtype not in _DTYPES:
+        raise ValueError("head_dim must be contiguous; dtype float32, bfloat16 or float16")
+    if block_table.dtype != torch.int32 or block_table.dim() != 2 or not block_table.is_contiguous():
+        raise ValueError("block_table must be a contiguous int32 tensor [B, max_blocks]")
+    B, L, Hq, Tq, d = q.shape
+    if len(pools) != L or block_table.shape[0] != B or p0.shape[3] != d:
+        raise ValueError("q, the pools and the block table disagree on batch, layers or head_dim")
+    shp = KrulShape(B, L, Hq, p0.shape[2], d, int(n_hist), Tq, _DTYPES[q.dtype], float(scale), int(flags))
+    if k_table is None:
+        k_table = torch.tensor([t.data_ptr() for t in pools], dtype=torch.int64).to(q.device)
+    pages = KrulKPages(k_table.data_ptr(), block_table.data_ptr(), p0.shape[1], block_table.shape[1],
+                       p0.stride(0), p0.stride(2), p0.stride(1))
+    need = workspace_bytes(shp)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ps = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
+    hs = torch.empty((B, L - 1, Hq), dtype=torch.float32, device=q.device) if want_head_score else None
+    pd = torch.empty((B, L - 1), dtype=torch.float32, device=q.device) if want_pair_dist else None
+    rc = lib().krul_pair_similarity_paged(ctypes.byref(shp), _dev_ptr(q), ctypes.byref(pages), _dev_ptr(ps),
+                                          _dev_ptr(hs), _dev_ptr(pd), _dev_ptr(workspace),
+                                          workspace.numel() if workspace is not None else 0,
+                                          ctypes.c_void_p(_stream_ptr()))
     if rc != KRUL_OK:
         raise KrulError(rc)
     return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace, "k_table": k_table}

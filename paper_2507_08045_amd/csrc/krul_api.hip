@@ -134,14 +134,18 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
                    float *head_score, float *pair_dist, bool ir, float gamma, float *ir_mass,
                    uint8_t *eligible, void *workspace, size_t workspace_bytes, void *stream,
                    void *event_begin, void *event_end, bool accumulate = false,
-                   const krul_k_layout_t *kl = nullptr)
+                   const krul_k_layout_t *kl = nullptr, const krul_k_pages_t *kp = nullptr)
 {
     Plan pl;
     const int rc = make_plan(shape, &pl, ir);
     if (rc != KRUL_OK) return rc;
-    if (!q || (kl ? !kl->k_layers : !k) || (accumulate ? !head_score : !pair_score)) return KRUL_EINVAL;
+    if (!q || (kp ? (!kp->k_layers || !kp->block_table) : kl ? !kl->k_layers : !k) ||
+        (accumulate ? !head_score : !pair_score))
+        return KRUL_EINVAL;
     if (ir && (shape->flags & KRUL_FLAG_CAUSAL)) return KRUL_EUNSUPPORTED;
-    if (((uintptr_t)q | (uintptr_t)k) & 15 || (kl && ((uintptr_t)kl->k_layers & 7))) return KRUL_EINVAL;
+    if (((uintptr_t)q | (uintptr_t)k) & 15 || (kl && ((uintptr_t)kl->k_layers & 7)) ||
+        (kp && (((uintptr_t)kp->k_layers & 7) || ((uintptr_t)kp->block_table & 3))))
+        return KRUL_EINVAL;
     if (((uintptr_t)pair_score | (uintptr_t)head_score | (uintptr_t)pair_dist | (uintptr_t)ir_mass) & 3)
         return KRUL_EINVAL;
     if (ir && (!(gamma >= 0.f) || !isfinite(gamma) || (!ir_mass && !eligible))) return KRUL_EINVAL;
@@ -178,6 +182,9 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     {
         const long long d = p.d, S = p.S;
         p.k_tab = nullptr;
+        p.block_table = nullptr;
+        p.page_shift = p.max_blocks = 0;
+        p.k_stride_page = 0;
         p.k_stride_l = (long long)p.Hkv * S * d;
         p.k_stride_b = (long long)p.L * p.Hkv * S * d;
         p.k_stride_h = S * d;
@@ -196,6 +203,22 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
             p.k_stride_b = p.B > 1 ? kl->k_stride_b : 0;
             p.k_stride_h = kl->k_stride_h;
             p.k_stride_s = kl->k_stride_s;
+        } else if (kp) {
+            const int bs = kp->block_size;
+            if (bs < 8 || (bs & (bs - 1)) || kp->max_blocks < (S + bs - 1) / bs || kp->k_stride_block <= 0 ||
+                kp->k_stride_h <= 0 || kp->k_stride_s < d || ((kp->k_stride_block | kp->k_stride_h | kp->k_stride_s) & 7))
+                return KRUL_EINVAL;
+            // (row swizzle; 32-bit byte offsets over the keys one copy instruction moves)
+            if (pl.lay.variant != kGeneric && (kp->k_stride_s % d != 0 || kp->k_stride_s >= (1ll << 27)))
+                return KRUL_EUNSUPPORTED;
+            p.k_tab = kp->k_layers;
+            p.block_table = kp->block_table;
+            p.max_blocks = kp->max_blocks;
+            for (p.page_shift = 3; (1 << p.page_shift) < bs; ++p.page_shift) {}
+            p.k_stride_page = kp->k_stride_block;
+            p.k_stride_l = p.k_stride_b = 0;
+            p.k_stride_h = kp->k_stride_h;
+            p.k_stride_s = kp->k_stride_s;
         } else if (pl.lay.variant != kGeneric && S * d * 2 >= (1ll << 31)) {
             return KRUL_EUNSUPPORTED;
         }
@@ -292,6 +315,15 @@ int krul_select_pairs_all(const float *score, int32_t closer_is_smaller, const u
     const hipError_t e = launch_select_all(score, closer_is_smaller, eligible, batch, n_layers, n_select, out_pairs,
                                            out_count, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
+}
+
+int krul_pair_similarity_paged(const krul_shape_t *shape, const void *q, const krul_k_pages_t *k_pages,
+                               float *pair_score, float *head_score, float *pair_dist,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!k_pages) return KRUL_EINVAL;
+    return run_similarity(shape, q, nullptr, pair_score, head_score, pair_dist, false, 0.f, nullptr, nullptr,
+                          workspace, workspace_bytes, stream, nullptr, nullptr, false, nullptr, k_pages);
 }
 
 int krul_pair_similarity_accumulate(const krul_shape_t *shape, const void *q, const void *k,

@@ -83,6 +83,12 @@ struct SimParams {
     // (b, kv head, j) starts at b * k_stride_b + kvh * k_stride_h + j * k_stride_s, head_dim contiguous.
     const void *const *k_tab;
     long long k_stride_l, k_stride_b, k_stride_h, k_stride_s;
+    // Paged keys (k_tab set as well: one pool of pages per layer): key j of conversation b is key
+    // j % 2^page_shift of page block_table[b * max_blocks + (j >> page_shift)]; a page starts k_stride_page
+    // elements after the one before, its keys are k_stride_s apart, kv heads k_stride_h.
+    const int *block_table;
+    int page_shift, max_blocks;
+    long long k_stride_page;
     int ir_init_end, ir_recent_begin;
     float *state_ir, *spill_ir;
     StateLayout lay;

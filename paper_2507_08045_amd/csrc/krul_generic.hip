@@ -131,7 +131,12 @@ __global__ __launch_bounds__(64) void sim_generic_kernel(SimParams p)
             float x = -INFINITY;
             if (valid) {
                 const T *kl = p.k_tab ? static_cast<const T *>(p.k_tab[l]) : K + (size_t)l * p.k_stride_l;
-                const size_t koff = (size_t)b * p.k_stride_b + (size_t)kvh * p.k_stride_h + (size_t)key * p.k_stride_s;
+                size_t koff = (size_t)kvh * p.k_stride_h;
+                if (p.block_table)   // paged keys
+                    koff += (size_t)p.block_table[(size_t)b * p.max_blocks + (key >> p.page_shift)] * p.k_stride_page +
+                            (size_t)(key & ((1 << p.page_shift) - 1)) * p.k_stride_s;
+                else
+                    koff += (size_t)b * p.k_stride_b + (size_t)key * p.k_stride_s;
                 x = dot_row<T>(qs, kl + koff, p.d) * p.c;
             }
             const float4 cur = st[l];

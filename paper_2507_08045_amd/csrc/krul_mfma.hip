@@ -118,7 +118,10 @@ __device__ inline f32x16 mfma_16bit(bf16x8 a, bf16x8 b, f32x16 c)
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-template <class C, int MODE, bool SK, bool F16>
+// KA: how the keys are addressed.  0: dense [B][L][Hkv][S][d].  1: one allocation per layer (a device
+// table of pointers) and strides between conversations, kv heads and keys.  2: one pool of pages per
+// layer, a block table per conversation, strides between pages, kv heads and the keys of a page.
+template <class C, int MODE, int KA, bool F16>
 __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 {
     constexpr int D = C::D, WK = C::WK, KBW = C::KBW, NC = C::NC, KS = C::KS;
@@ -173,9 +176,12 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     // Keys of layer l, this unit: k_layer(l) + k_tile_off, where k_tile_off leads to the unit's first key
     // of the tile being fetched (see SimParams).  Layer and tile advance by additions, so that the dense
     // layout costs no multiplications inside the loop.
-    const size_t k_stride_s = SK ? (size_t)p.k_stride_s : (size_t)D;   // SK: keys with strides, layers from a table
-    size_t k_tile_off = (size_t)b * p.k_stride_b + (size_t)kvh * p.k_stride_h + (size_t)key_begin * k_stride_s;
-    const size_t k_tile_step = (size_t)C::KT * k_stride_s;
+    constexpr bool SK = KA != 0;   // keys with strides, layers from a table
+    const size_t k_stride_s = SK ? (size_t)p.k_stride_s : (size_t)D;
+    // (paged: the page and the key inside it are added per copy instruction; only the head is fixed)
+    size_t k_tile_off = KA == 2 ? (size_t)kvh * p.k_stride_h
+                                : (size_t)b * p.k_stride_b + (size_t)kvh * p.k_stride_h + (size_t)key_begin * k_stride_s;
+    const size_t k_tile_step = KA == 2 ? 0 : (size_t)C::KT * k_stride_s;
     const uint16_t *k_dense = Kg;   // dense layout: the layer being fetched starts here
     auto k_layer = [&](int l) __attribute__((always_inline)) -> const uint16_t * {
         // the table is read as constant memory at a uniform address: a scalar load, which takes no place in
@@ -202,9 +208,34 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     // layer and key tile (fetch_k), with the tile's first key (fetch_key0).
     const uint16_t *fetch_k = uniform_ptr(k_layer(0) + k_tile_off);
     int fetch_key0 = key_begin;
+    // Paged keys: a copy instruction moves RPI whole keys, which lie in one page (pages hold a power of
+    // two >= 8 keys and tiles start on multiples of them); its page comes from the conversation's block
+    // table by a scalar load, and it gets a descriptor of its own, bounded by the keys that exist.
+    const unsigned ld_offp = (unsigned)(lane / PPR) * k_row_bytes + (unsigned)(((lane % PPR) ^ swz<D>(ld_row0)) * 16);
+    typedef const __attribute__((address_space(4))) int *const_i32_ptr;
+    const const_i32_ptr page_row = KA == 2 ? (const_i32_ptr)(uintptr_t)(p.block_table + (size_t)b * p.max_blocks) : nullptr;
     auto issue_chunk = [&](int c, bool live) __attribute__((always_inline)) {
         unsigned char *dst = slot_ptr(c);
         const int key0 = fetch_key0 + c * C::CH;
+        if constexpr (KA == 2) {
+            const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) {
+                const int krow = key0 + (wave_u * NLD + j) * RPI;        // first key of this instruction
+                const int kcl = min(krow, S - 1);
+                const int pid = page_row[kcl >> p.page_shift];
+                const uint16_t *base = fetch_k + (size_t)pid * p.k_stride_page +
+                                       (size_t)(kcl & ((1 << p.page_shift) - 1)) * k_stride_s;
+                const int rows = live ? min(max(S - krow, 0), RPI) : 0;
+                const unsigned bytes = rows ? (unsigned)(rows - 1) * k_row_bytes + (unsigned)(D * 2) : 0u;
+                const __amdgpu_buffer_rsrc_t rsrc =
+                    __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rsrc, (__attribute__((address_space(3))) void *)(dst + (wave * NLD + j) * 1024), 16,
+                    (int)(ld_offp ^ xj(j)), 0, 0, 0);
+            }
+            return;
+        }
         // Buffer addressing: a scalar descriptor for the rest of this layer's keys (rows past
         // the last key are out of range and are not fetched), one 32-bit offset per lane.
         // (a chunk past the end of the split gets an empty range: nothing is fetched)
@@ -555,17 +586,22 @@ template <class C, bool F16>
 hipError_t launch_cfg_t(const SimParams &p, int n_workgroups, hipStream_t st)
 {
     const dim3 grid(n_workgroups), block(C::THREADS);
-    if (p.k_tab) {   // keys in per-layer allocations, with strides (never with the Initial-Recent test)
+    if (p.block_table) {   // keys in pages (never with the Initial-Recent test)
         if (p.want_dist)
-            hipLaunchKernelGGL((sim_mfma_kernel<C, 1, true, F16>), grid, block, 0, st, p);
+            hipLaunchKernelGGL((sim_mfma_kernel<C, 1, 2, F16>), grid, block, 0, st, p);
         else
-            hipLaunchKernelGGL((sim_mfma_kernel<C, 0, true, F16>), grid, block, 0, st, p);
+            hipLaunchKernelGGL((sim_mfma_kernel<C, 0, 2, F16>), grid, block, 0, st, p);
+    } else if (p.k_tab) {   // keys in per-layer allocations, with strides (never with the Initial-Recent test)
+        if (p.want_dist)
+            hipLaunchKernelGGL((sim_mfma_kernel<C, 1, 1, F16>), grid, block, 0, st, p);
+        else
+            hipLaunchKernelGGL((sim_mfma_kernel<C, 0, 1, F16>), grid, block, 0, st, p);
     } else if (p.want_ir)
-        hipLaunchKernelGGL((sim_mfma_kernel<C, 2, false, F16>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 2, 0, F16>), grid, block, 0, st, p);
     else if (p.want_dist)
-        hipLaunchKernelGGL((sim_mfma_kernel<C, 1, false, F16>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 1, 0, F16>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((sim_mfma_kernel<C, 0, false, F16>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((sim_mfma_kernel<C, 0, 0, F16>), grid, block, 0, st, p);
     return hipGetLastError();
 }
 

@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(kr):
             "krul_pair_similarity_ir", "krul_pair_similarity_ir_workspace",
             "krul_pair_similarity_accumulate", "krul_pair_scores_from_sums",
             "krul_pair_similarity_strided", "krul_all_pairs_similarity", "krul_all_pairs_workspace",
-            "krul_select_pairs_all"} <= set(names)
+            "krul_select_pairs_all", "krul_pair_similarity_paged"} <= set(names)
     lib = kr.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in krul.h but not exported"
@@ -149,6 +149,28 @@ def test_strided_entry_point_rejects_bad_arguments_before_any_gpu_work(kr):
     assert call(shape(kr, B=2, flags=kr.KRUL_FLAG_GENERIC_KERNEL), ss=136, ws_bytes=16) == kr.KRUL_EWORKSPACE
     assert call(shape(kr, B=1), sb=0, ws_bytes=16) == kr.KRUL_EWORKSPACE   # one conversation: k_stride_b unused
     assert call(shape(kr, Hq=3)) == kr.KRUL_EINVAL
+    assert call(ws_bytes=16) == kr.KRUL_EWORKSPACE
+
+
+def test_paged_entry_point_rejects_bad_arguments_before_any_gpu_work(kr):
+    vp = ctypes.c_void_p
+    ok = shape(kr, B=2)           # S = 256
+
+    def call(shp=ok, tab=0x2000, bt=0x4000, bs=16, mb=16, sp=1 << 14, sh=128, ss=256, pages=True, ws_bytes=1 << 40):
+        kp = kr.KrulKPages(tab, bt, bs, mb, sp, sh, ss)
+        return kr.lib().krul_pair_similarity_paged(ctypes.byref(shp), vp(0x1000), ctypes.byref(kp) if pages else None,
+                                                   vp(0x3000), None, None, vp(0x10000), ctypes.c_size_t(ws_bytes), None)
+    assert call(pages=False) == kr.KRUL_EINVAL
+    assert call(tab=None) == kr.KRUL_EINVAL
+    assert call(bt=None) == kr.KRUL_EINVAL
+    assert call(bt=0x4002) == kr.KRUL_EINVAL            # int32 table
+    assert call(bs=12) == kr.KRUL_EINVAL                # pages hold a power of two of keys ...
+    assert call(bs=4) == kr.KRUL_EINVAL                 # ... at least 8
+    assert call(mb=15) == kr.KRUL_EINVAL                # 256 keys need 16 pages of 16
+    assert call(sp=0) == kr.KRUL_EINVAL
+    assert call(ss=64) == kr.KRUL_EINVAL                # keys would overlap
+    assert call(ss=136) == kr.KRUL_EUNSUPPORTED         # bf16 kernel: whole head_dims between keys
+    assert call(shape(kr, B=2, flags=kr.KRUL_FLAG_GENERIC_KERNEL), ss=136, ws_bytes=16) == kr.KRUL_EWORKSPACE
     assert call(ws_bytes=16) == kr.KRUL_EWORKSPACE
 
 
