@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--with-dist", action="store_true",
                     help="also ask for the Euclidean distance by-product (pair_dist)")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="score with krul_pair_similarity and select with krul_select_pairs, instead of the one "
+                         "call that does both (krul_pair_similarity_select)")
     ap.add_argument("--all-pairs", action="store_true",
                     help="time the all-pairs reading instead (every two layers scored, then the greedy choice "
                          "over all of them); not the headline metric")
@@ -163,10 +166,16 @@ def main():
     EV_EVERY = 4 if K >= 16 else 1
     evs = [(hipevents.create(), hipevents.create()) if i % EV_EVERY == 0 else None for i in range(K)]
 
+    out_sel = dict(out, pairs=pairs, count=count)
+
     def step(ev=None):
-        kr.pair_similarity(q, k, flags=args.flags, workspace=ws, out=out, events=ev,
-                           want_pair_dist=args.with_dist)
-        kr.select_pairs(out["pair_score"], w.n_select, out_pairs=pairs, out_count=count)
+        if args.two_calls:
+            kr.pair_similarity(q, k, flags=args.flags, workspace=ws, out=out, events=ev,
+                               want_pair_dist=args.with_dist)
+            kr.select_pairs(out["pair_score"], w.n_select, out_pairs=pairs, out_count=count)
+        else:   # the same two steps of Alg. 1 through the entry point that enqueues both
+            kr.pair_similarity_select(q, k, w.n_select, flags=args.flags, workspace=ws, out=out_sel, events=ev,
+                                      want_pair_dist=args.with_dist)
 
     for _ in range(args.warmup):
         step()
@@ -208,7 +217,8 @@ def main():
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} L={w.L} Hq/Hkv={w.Hq}/{w.Hkv} d={w.d} S={w.S} Tq={w.Tq} "
                                f"{w.dtype}, select {w.n_select} pairs", "score_elems": w.score_elems,
-                   "outputs": "pair_score+head_score" + ("+pair_dist" if args.with_dist else "")},
+                   "outputs": "pair_score+head_score" + ("+pair_dist" if args.with_dist else "") + "+pairs",
+                   "calls": "krul_pair_similarity + krul_select_pairs" if args.two_calls else "krul_pair_similarity_select"},
         "roofline": {"bound": "hbm", "achieved": hbm_gbs, "peak": 8000.0, "unit": "GB/s",
                      "frac": hbm_gbs / 8000.0, "traffic": traffic,
                      "kernel": "sim_mfma_kernel" if w.dtype == "bf16" and not (args.flags & 256) else "sim_generic_kernel",

@@ -239,6 +239,25 @@ int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
                       int32_t *out_pairs, int32_t *out_count, void *stream);
 
 /*
+ * Alg. 1's scoring and greedy choice (Sec. 4.2) in one call: krul_pair_similarity followed by
+ * krul_select_pairs on its pair_score, with the same results bit for bit.  When the problem is small
+ * (batch * (n_layers-1) * n_q_heads <= 4096 and batch <= 16) the averages over heads and the selection run
+ * in one single-workgroup kernel, which saves a launch of a few microseconds; otherwise the same kernels
+ * run as for the two calls.
+ *
+ *   eligible, n_select, out_pairs, out_count   as for krul_select_pairs (eligible is an input here: take it
+ *                                              from an earlier krul_pair_similarity_ir, or pass NULL)
+ *   event_begin, event_end                     as for krul_pair_similarity_timed, either may be NULL
+ *   everything else                            as for krul_pair_similarity
+ */
+int krul_pair_similarity_select(const krul_shape_t *shape, const void *q, const void *k,
+                                const uint8_t *eligible, int32_t n_select,
+                                float *pair_score, float *head_score, float *pair_dist,
+                                int32_t *out_pairs, int32_t *out_count,
+                                void *workspace, size_t workspace_bytes, void *stream,
+                                void *event_begin, void *event_end);
+
+/*
  * Similarity of EVERY two layers i > j, as Alg. 1 is printed ("for every two weights A_i, A_j (i > j)",
  * Sec. 4.2; the layer-by-layer similarity map of Sec. 2.3), not only of neighbours.  Same definitions as
  * krul_pair_similarity: per conversation, query head and query row the cosine and the Euclidean distance

@@ -81,6 +81,9 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_paged.restype = ctypes.c_int
         L.krul_pair_similarity_paged.argtypes = [ctypes.POINTER(KrulShape), vp, ctypes.POINTER(KrulKPages), vp, vp,
                                                  vp, vp, sz, vp]
+        L.krul_pair_similarity_select.restype = ctypes.c_int
+        L.krul_pair_similarity_select.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, ctypes.c_int32, vp, vp, vp,
+                                                  vp, vp, vp, sz, vp, vp, vp]
         L.krul_pair_similarity_accumulate.restype = ctypes.c_int
         L.krul_pair_similarity_accumulate.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, sz, vp]
         L.krul_pair_scores_from_sums.restype = ctypes.c_int
@@ -360,6 +363,46 @@ def select_pairs(pair_score: torch.Tensor, n_select: int, eligible: torch.Tensor
     if rc != KRUL_OK:
         raise KrulError(rc)
     return out_pairs, out_count
+
+
+def pair_similarity_select(q: torch.Tensor, k: torch.Tensor, n_select: int, eligible: torch.Tensor | None = None, *,
+                           scale: float = 0.0, flags: int = 0, want_head_score: bool = True,
+                           want_pair_dist: bool = True, workspace: torch.Tensor | None = None,
+                           out: dict | None = None, events: tuple | None = None) -> dict:
+    """krul_pair_similarity_select on the current stream: the outputs of pair_similarity plus
+    pairs [B,n_select] int32 and count [B] int32 of select_pairs on its pair_score."""
+    if not (q.is_cuda and k.is_cuda):
+        raise ValueError("q and k must be GPU tensors (this library has no CPU path)")
+    if not (q.is_contiguous() and k.is_contiguous()):
+        raise ValueError("q and k must be contiguous")
+    shp = make_shape(q, k, scale, flags)
+    B, L, Hq = shp.batch, shp.n_layers, shp.n_q_heads
+    if eligible is not None:
+        if not eligible.is_cuda or eligible.dtype != torch.uint8 or tuple(eligible.shape) != (B, L) \
+                or not eligible.is_contiguous():
+            raise ValueError("eligible must be a contiguous uint8 GPU tensor [B, n_layers]")
+    need = workspace_bytes(shp)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    out = out or {}
+
+    def buf(name, shape, dtype, wanted=True):
+        t = out.get(name)
+        return t if t is not None or not wanted else torch.empty(shape, dtype=dtype, device=q.device)
+    ps = buf("pair_score", (B, L - 1), torch.float32)
+    hs = buf("head_score", (B, L - 1, Hq), torch.float32, want_head_score)
+    pd = buf("pair_dist", (B, L - 1), torch.float32, want_pair_dist)
+    pairs = buf("pairs", (B, max(int(n_select), 0)), torch.int32)
+    count = buf("count", (B,), torch.int32)
+    ev = events or (None, None)
+    rc = lib().krul_pair_similarity_select(
+        ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), _dev_ptr(eligible), int(n_select), _dev_ptr(ps), _dev_ptr(hs),
+        _dev_ptr(pd), _dev_ptr(pairs), _dev_ptr(count), _dev_ptr(workspace),
+        workspace.numel() if workspace is not None else 0, ctypes.c_void_p(_stream_ptr()),
+        ctypes.c_void_p(ev[0]), ctypes.c_void_p(ev[1]))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "pairs": pairs, "count": count, "workspace": workspace}
 
 
 def all_pairs_workspace_bytes(shape: KrulShape, max_bytes: int = 0) -> int:

@@ -126,6 +126,13 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__re
 }  // namespace
 
 namespace {
+// Selection asked for in the same call (krul_pair_similarity_select).
+struct SelectArgs {
+    const uint8_t *eligible;
+    int n_select;
+    int32_t *out_pairs, *out_count;
+};
+
 // The one implementation behind the similarity entry points.  ir: also run the Initial-Recent layer
 // test (gamma, ir_mass, eligible as for krul_pair_similarity_ir).
 // accumulate: head_score / pair_dist are the caller's running sums [B][L-1][Hq] (see
@@ -134,7 +141,8 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
                    float *head_score, float *pair_dist, bool ir, float gamma, float *ir_mass,
                    uint8_t *eligible, void *workspace, size_t workspace_bytes, void *stream,
                    void *event_begin, void *event_end, bool accumulate = false,
-                   const krul_k_layout_t *kl = nullptr, const krul_k_pages_t *kp = nullptr)
+                   const krul_k_layout_t *kl = nullptr, const krul_k_pages_t *kp = nullptr,
+                   const SelectArgs *sel = nullptr)
 {
     Plan pl;
     const int rc = make_plan(shape, &pl, ir);
@@ -234,9 +242,23 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
         return KRUL_ELAUNCH;
     float *head_cos = head_score ? head_score : reinterpret_cast<float *>(ws + pl.head_cos_off);
     float *head_dist = accumulate ? pair_dist : reinterpret_cast<float *>(ws + pl.head_dist_off);
+    if (sel && pairs_select_fits(p.B, p.L, p.Hq)) {   // head scores, then pairs and selection in one small launch
+        e = launch_finalize(pl.lay, p.state, p.B, p.L, p.Hq, p.Hkv, p.Tq, head_cos, head_dist, nullptr,
+                            pair_dist, false, st);
+        if (e == hipSuccess) {
+            const PairsSelectArgs a = {head_cos, pair_dist ? head_dist : nullptr, pair_score, pair_dist, sel->eligible,
+                                       p.B, p.L, p.Hq, sel->n_select, sel->out_pairs, sel->out_count};
+            e = launch_pairs_select(a, st);
+        }
+        return e == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
+    }
     e = launch_finalize(pl.lay, p.state, p.B, p.L, p.Hq, p.Hkv, p.Tq, head_cos, head_dist,
                         pair_score, pair_dist, accumulate, st);
     if (e != hipSuccess) return KRUL_ELAUNCH;
+    if (sel) {
+        e = launch_select(pair_score, sel->eligible, p.B, p.L, sel->n_select, sel->out_pairs, sel->out_count, st);
+        if (e != hipSuccess) return KRUL_ELAUNCH;
+    }
     if (ir) {
         e = launch_finalize_ir(pl.lay, p.state, p.state_ir, p.B, p.L, p.Hq, p.Hkv, p.Tq, gamma,
                                reinterpret_cast<float *>(ws + pl.head_ir_off), ir_mass, eligible, st);
@@ -315,6 +337,21 @@ int krul_select_pairs_all(const float *score, int32_t closer_is_smaller, const u
     const hipError_t e = launch_select_all(score, closer_is_smaller, eligible, batch, n_layers, n_select, out_pairs,
                                            out_count, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
+}
+
+int krul_pair_similarity_select(const krul_shape_t *shape, const void *q, const void *k,
+                                const uint8_t *eligible, int32_t n_select,
+                                float *pair_score, float *head_score, float *pair_dist,
+                                int32_t *out_pairs, int32_t *out_count,
+                                void *workspace, size_t workspace_bytes, void *stream,
+                                void *event_begin, void *event_end)
+{
+    if (!shape || !out_count || n_select < 0 || n_select > shape->n_layers / 2 || (n_select > 0 && !out_pairs))
+        return KRUL_EINVAL;
+    if (((uintptr_t)out_pairs | (uintptr_t)out_count) & 3) return KRUL_EINVAL;
+    const SelectArgs sel = {eligible, n_select, out_pairs, out_count};
+    return run_similarity(shape, q, k, pair_score, head_score, pair_dist, false, 0.f, nullptr, nullptr,
+                          workspace, workspace_bytes, stream, event_begin, event_end, false, nullptr, nullptr, &sel);
 }
 
 int krul_pair_similarity_paged(const krul_shape_t *shape, const void *q, const krul_k_pages_t *k_pages,

@@ -216,7 +216,7 @@ hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, i
     hipLaunchKernelGGL(finalize_heads_kernel, dim3(n_pairs_total * Hq), dim3(kThreads), 0, st, lay,
                        state, L, Hq, Hkv, Tq, G, pair_dist != nullptr, accumulate ? 1 : 0, head_cos, head_dist);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || accumulate) return e;
+    if (e != hipSuccess || accumulate || !pair_cos) return e;   // (no pair scores asked for: the caller forms them)
     hipLaunchKernelGGL(finalize_pairs_kernel, dim3((n_pairs_total + 127) / 128), dim3(128), 0, st,
                        n_pairs_total, Hq, 1.0f, head_cos, head_dist, (float *)nullptr, pair_cos, pair_dist);
     return hipGetLastError();

@@ -1,12 +1,7 @@
-// Greedy disjoint layer-pair selection (Alg. 1, second loop; Sec. 4.2).
-//
-// One workgroup per conversation.  The candidates (adjacent pairs whose two layers
-// are eligible) are ranked by counting: rank(l) = number of candidates that come
-// before l in the order "higher score first, equal scores lower index first".  That
-// is the stable descending sort the algorithm asks for, with no data-dependent
-// control flow.  One thread then scans the ranked list and takes a pair iff both
-// its layers are still free, until n_select pairs are held.
+// Greedy disjoint layer-pair selection (Alg. 1, second loop; Sec. 4.2): one workgroup per
+// conversation; the method itself is select_adjacent() in krul_select_core.h.
 #include "krul_common.h"
+#include "krul_select_core.h"
 
 namespace krul {
 namespace {
@@ -20,57 +15,62 @@ __global__ __launch_bounds__(kSelThreads) void select_pairs_kernel(
     extern __shared__ unsigned char sel_smem[];
     const int NP = n_layers - 1;
     float *score = reinterpret_cast<float *>(sel_smem);          // [NP]
-    int32_t *order = reinterpret_cast<int32_t *>(score + NP);    // [NP] candidate at each rank
-    uint8_t *cand = reinterpret_cast<uint8_t *>(order + NP);     // [NP]
-    uint8_t *used = cand + NP;                                   // [n_layers]
-
     const int b = blockIdx.x;
-    const float *sc = pair_score + (size_t)b * NP;
-    const uint8_t *el = eligible ? eligible + (size_t)b * n_layers : nullptr;
+    for (int l = threadIdx.x; l < NP; l += kSelThreads) score[l] = pair_score[(size_t)b * NP + l];
+    select_adjacent(score, eligible ? eligible + (size_t)b * n_layers : nullptr, n_layers, n_select,
+                    out_pairs + (size_t)b * n_select, out_count + b, score + NP);
+}
 
-    for (int l = threadIdx.x; l < NP; l += kSelThreads) {
-        score[l] = sc[l];
-        cand[l] = (!el || (el[l] && el[l + 1])) ? 1 : 0;
-        order[l] = -1;
-    }
-    for (int l = threadIdx.x; l < n_layers; l += kSelThreads) used[l] = 0;
-    __syncthreads();
-
-    for (int l = threadIdx.x; l < NP; l += kSelThreads) {
-        if (!cand[l]) continue;
-        const float s = score[l];
-        int rank = 0;
-        for (int j = 0; j < NP; ++j) {
-            if (!cand[j]) continue;
-            const float sj = score[j];
-            // j precedes l unless l's score is strictly higher, or equal with l first
-            rank += (sj > s || (!(sj < s) && j < l)) ? 1 : 0;
-        }
-        order[rank] = l;
+// Averages over the heads (in order, as finalize_pairs_kernel takes them: the same bits) and the greedy
+// choice of every conversation in one workgroup: for small problems, where each further launch costs
+// more than the work in it.
+__global__ __launch_bounds__(kSelThreads) void pairs_select_kernel(PairsSelectArgs a)
+{
+    extern __shared__ unsigned char sel_smem[];
+    const int NP = a.L - 1, n_pairs_total = a.B * NP, n = n_pairs_total * a.Hq;
+    float *vc = reinterpret_cast<float *>(sel_smem);   // [n] head cosines
+    float *vd = vc + n;                                // [n] head distances
+    float *pc = vd + n;                                // [n_pairs_total] pair scores
+    for (int i = threadIdx.x; i < n; i += kSelThreads) {
+        vc[i] = a.head_cos[i];
+        if (a.head_dist) vd[i] = a.head_dist[i];
     }
     __syncthreads();
-
-    if (threadIdx.x == 0) {
-        int cnt = 0;
-        for (int i = 0; i < NP && cnt < n_select; ++i) {
-            const int l = order[i];
-            if (l < 0) break;  // ranks are dense: first hole = end of candidates
-            if (used[l] || used[l + 1]) continue;
-            used[l] = used[l + 1] = 1;
-            out_pairs[(size_t)b * n_select + cnt++] = l;
+    for (int i = threadIdx.x; i < n_pairs_total; i += kSelThreads) {
+        float cs = 0.f, ds = 0.f;
+#pragma unroll 8
+        for (int h = 0; h < a.Hq; ++h) {
+            cs += vc[i * a.Hq + h];
+            if (a.head_dist) ds += vd[i * a.Hq + h];
         }
-        out_count[b] = cnt;
-        for (int i = cnt; i < n_select; ++i) out_pairs[(size_t)b * n_select + i] = -1;
+        a.pair_cos[i] = pc[i] = cs / (float)a.Hq;
+        if (a.head_dist) a.pair_dist[i] = ds / (float)a.Hq;
     }
+    for (int b = 0; b < a.B; ++b)   // (select_adjacent starts and ends with a barrier)
+        select_adjacent(pc + b * NP, a.eligible ? a.eligible + (size_t)b * a.L : nullptr, a.L, a.n_select,
+                        a.out_pairs + (size_t)b * a.n_select, a.out_count + b, pc + n_pairs_total);
 }
 
 }  // namespace
+
+bool pairs_select_fits(int B, int L, int Hq)
+{
+    return (long long)B * (L - 1) * Hq <= kPairsSelectMaxHeads && B <= kPairsSelectMaxBatch;
+}
+
+hipError_t launch_pairs_select(const PairsSelectArgs &a, hipStream_t st)
+{
+    const int n_pairs_total = a.B * (a.L - 1);
+    const size_t smem = (size_t)(2 * n_pairs_total * a.Hq + n_pairs_total) * sizeof(float) + select_scratch_bytes(a.L);
+    hipLaunchKernelGGL(pairs_select_kernel, dim3(1), dim3(kSelThreads), smem, st, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_select(const float *pair_score, const uint8_t *eligible, int batch, int n_layers,
                          int n_select, int32_t *out_pairs, int32_t *out_count, hipStream_t st)
 {
     const int NP = n_layers - 1;
-    const size_t smem = (size_t)NP * (sizeof(float) + sizeof(int32_t) + 1) + n_layers;
+    const size_t smem = (size_t)NP * sizeof(float) + select_scratch_bytes(n_layers);
     hipLaunchKernelGGL(select_pairs_kernel, dim3(batch), dim3(kSelThreads), smem, st, pair_score,
                        eligible, n_layers, n_select, out_pairs, out_count);
     return hipGetLastError();

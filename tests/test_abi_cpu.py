@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(kr):
             "krul_pair_similarity_ir", "krul_pair_similarity_ir_workspace",
             "krul_pair_similarity_accumulate", "krul_pair_scores_from_sums",
             "krul_pair_similarity_strided", "krul_all_pairs_similarity", "krul_all_pairs_workspace",
-            "krul_select_pairs_all", "krul_pair_similarity_paged"} <= set(names)
+            "krul_select_pairs_all", "krul_pair_similarity_paged", "krul_pair_similarity_select"} <= set(names)
     lib = kr.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in krul.h but not exported"
@@ -171,6 +171,24 @@ def test_paged_entry_point_rejects_bad_arguments_before_any_gpu_work(kr):
     assert call(ss=64) == kr.KRUL_EINVAL                # keys would overlap
     assert call(ss=136) == kr.KRUL_EUNSUPPORTED         # bf16 kernel: whole head_dims between keys
     assert call(shape(kr, B=2, flags=kr.KRUL_FLAG_GENERIC_KERNEL), ss=136, ws_bytes=16) == kr.KRUL_EWORKSPACE
+    assert call(ws_bytes=16) == kr.KRUL_EWORKSPACE
+
+
+def test_select_in_one_call_rejects_bad_arguments_before_any_gpu_work(kr):
+    vp = ctypes.c_void_p
+    ok = shape(kr)           # 4 layers
+
+    def call(shp=ok, n_select=2, pairs=0x5000, count=0x6000, ps=0x3000, ws_bytes=1 << 40):
+        return kr.lib().krul_pair_similarity_select(
+            ctypes.byref(shp) if shp is not None else None, vp(0x1000), vp(0x2000), None, n_select, vp(ps), None, None,
+            vp(pairs), vp(count), vp(0x10000), ctypes.c_size_t(ws_bytes), None, None, None)
+    assert call(shp=None) == kr.KRUL_EINVAL
+    assert call(n_select=-1) == kr.KRUL_EINVAL
+    assert call(n_select=3) == kr.KRUL_EINVAL          # more pairs than 4 layers hold
+    assert call(count=None) == kr.KRUL_EINVAL
+    assert call(pairs=None) == kr.KRUL_EINVAL
+    assert call(pairs=0x5002) == kr.KRUL_EINVAL
+    assert call(ps=None) == kr.KRUL_EINVAL
     assert call(ws_bytes=16) == kr.KRUL_EWORKSPACE
 
 

@@ -1,0 +1,95 @@
+"""GPU parity of krul_pair_similarity_select (Alg. 1's scoring and greedy choice, Sec. 4.2, in one call)
+against the fp64 oracle and, bit for bit, against the two calls it stands for."""
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return gpu_util
+
+
+# (name, B, L, Hq, Hkv, d, S, Tq, dtype, n_select, with_eligible)
+CASES = [
+    ("sel-wide", 1, 12, 8, 2, 128, 1500, 40, "bf16", 4, False),        # several key splits, one conversation
+    ("sel-batch", 3, 9, 4, 2, 64, 700, 6, "bf16", 3, True),            # three conversations in the last workgroup
+    ("sel-f32", 2, 6, 4, 2, 64, 300, 5, "f32", 2, True),               # portable similarity kernel
+    ("sel-two-layers", 1, 2, 2, 1, 64, 40, 1, "bf16", 1, False),
+    ("sel-none", 2, 5, 4, 4, 128, 90, 2, "f16", 0, False),             # n_select = 0
+    ("sel-many-heads", 2, 40, 64, 8, 64, 200, 1, "bf16", 10, True),    # 2*39*64 = 4992 head values: separate kernels
+    ("sel-many-conversations", 20, 4, 2, 2, 64, 130, 2, "bf16", 2, True),   # batch > 16: separate kernels
+    ("sel-at-the-limit", 2, 33, 64, 8, 64, 150, 1, "bf16", 16, False),  # 2*32*64 = 4096: the largest fused case
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_select_fused_matches_two_calls_and_oracle(G, oracle, case):
+    import paper_2507_08045_amd as kr
+    name, B, L, Hq, Hkv, d, S, Tq, dtype, n_select, with_el = case
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    rho = rng.uniform(0.3, 0.95, size=(B, L - 1, Hkv))
+    w = workloads.make(name, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, dtype=dtype, rho_k=rho, seed=131)
+    q, k = G.to_device(w)
+    el = (rng.random((B, L)) > 0.2).astype(np.uint8) if with_el else None
+    el_gpu = torch.from_numpy(el).cuda() if with_el else None
+
+    ref = kr.pair_similarity(q, k)
+    ref_pairs, ref_count = kr.select_pairs(ref["pair_score"], n_select, el_gpu)
+    torch.cuda.synchronize()
+
+    ws = torch.empty(kr.workspace_bytes(kr.make_shape(q, k)), dtype=torch.uint8, device="cuda")
+    for trial, fill in enumerate((0xFF, 0x00, None)):     # whatever the workspace held before
+        if fill is not None:
+            ws.fill_(fill)
+        out = kr.pair_similarity_select(q, k, n_select, el_gpu, workspace=ws)
+        torch.cuda.synchronize()
+        for n in ("pair_score", "head_score", "pair_dist"):
+            np.testing.assert_array_equal(out[n].cpu().numpy(), ref[n].cpu().numpy(), err_msg=f"{name} {n} trial {trial}")
+        np.testing.assert_array_equal(out["pairs"].cpu().numpy(), ref_pairs.cpu().numpy())
+        np.testing.assert_array_equal(out["count"].cpu().numpy(), ref_count.cpu().numpy())
+
+    want = oracle.pair_similarity(w.q, w.k)
+    G.assert_close(out["pair_score"].cpu().numpy(), want["pair_score"], G.TOL, f"{name} pair_score")
+    G.assert_close(out["pair_dist"].cpu().numpy(), want["pair_dist"], G.TOL, f"{name} pair_dist")
+    wp, wc = oracle.select_pairs(out["pair_score"].cpu().numpy().astype(np.float64), n_select, el)
+    np.testing.assert_array_equal(out["pairs"].cpu().numpy(), wp)
+    np.testing.assert_array_equal(out["count"].cpu().numpy(), wc)
+
+    # cosine only (no distance), no head scores returned
+    out2 = kr.pair_similarity_select(q, k, n_select, el_gpu, workspace=ws, want_head_score=False, want_pair_dist=False)
+    ref2 = kr.pair_similarity(q, k, want_head_score=False, want_pair_dist=False)
+    p2, c2 = kr.select_pairs(ref2["pair_score"], n_select, el_gpu)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out2["pair_score"].cpu().numpy(), ref2["pair_score"].cpu().numpy())
+    np.testing.assert_array_equal(out2["pairs"].cpu().numpy(), p2.cpu().numpy())
+    np.testing.assert_array_equal(out2["count"].cpu().numpy(), c2.cpu().numpy())
+
+
+def test_select_fused_c2_full_size(G, oracle):
+    """The benchmark's configuration, in the form bench.py times: scores of sampled (head, pair) units
+    against the oracle, the selection bit for bit against the oracle's selector on the same scores."""
+    import paper_2507_08045_amd as kr
+    w = workloads.config("C2")
+    q, k = G.to_device(w)
+    out = kr.pair_similarity_select(q, k, w.n_select)
+    ref = kr.pair_similarity(q, k)
+    torch.cuda.synchronize()
+    ps = out["pair_score"].cpu().numpy()
+    np.testing.assert_array_equal(ps, ref["pair_score"].cpu().numpy())
+    units = [(0, 3, 7), (0, 17, 30), (0, 30, 12)]           # (conversation, pair, query head)
+    uc, _ = oracle.unit_scores(w.q, w.k, units)
+    hs = out["head_score"].cpu().numpy()
+    for (b, l, h), c in zip(units, uc):
+        assert abs(hs[b, l, h] - c) <= G.TOL
+    wp, wc = oracle.select_pairs(ps.astype(np.float64), w.n_select)
+    np.testing.assert_array_equal(out["pairs"].cpu().numpy(), wp)
+    np.testing.assert_array_equal(out["count"].cpu().numpy(), wc)
