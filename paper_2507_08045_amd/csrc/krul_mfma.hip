@@ -211,9 +211,29 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     // Paged keys: a copy instruction moves RPI whole keys, which lie in one page (pages hold a power of
     // two >= 8 keys and tiles start on multiples of them); its page comes from the conversation's block
     // table by a scalar load, and it gets a descriptor of its own, bounded by the keys that exist.
+    // (On this chip the scalar offset of a buffer instruction takes part in the range check, like the
+    // lane offset: the dense path below relies on that.)
     const unsigned ld_offp = (unsigned)(lane / PPR) * k_row_bytes + (unsigned)(((lane % PPR) ^ swz<D>(ld_row0)) * 16);
     typedef const __attribute__((address_space(4))) int *const_i32_ptr;
     const const_i32_ptr page_row = KA == 2 ? (const_i32_ptr)(uintptr_t)(p.block_table + (size_t)b * p.max_blocks) : nullptr;
+    // Where each copy instruction of a tile starts, relative to the layer's pool (wave-uniform, in scalar
+    // registers).  Every layer has the same pages, so the table is read once per tile, not once per
+    // layer step: a lookup inside the step would make the wave wait for the scalar load at every chunk.
+    long long page_off[KA == 2 ? NC : 1][KA == 2 ? NLD : 1];   // in elements
+    auto load_pages = [&](int tile_key0) __attribute__((always_inline)) {
+        if constexpr (KA == 2) {
+            const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+#pragma unroll
+                for (int j = 0; j < NLD; ++j) {
+                    const int kcl = min(tile_key0 + c * C::CH + (wave_u * NLD + j) * RPI, S - 1);   // (stay inside the table row)
+                    page_off[c][j] = (long long)page_row[kcl >> p.page_shift] * p.k_stride_page +
+                                     (long long)(kcl & ((1 << p.page_shift) - 1)) * (long long)k_stride_s;
+                }
+        }
+    };
+    load_pages(key_begin);
     auto issue_chunk = [&](int c, bool live) __attribute__((always_inline)) {
         unsigned char *dst = slot_ptr(c);
         const int key0 = fetch_key0 + c * C::CH;
@@ -222,12 +242,13 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 #pragma unroll
             for (int j = 0; j < NLD; ++j) {
                 const int krow = key0 + (wave_u * NLD + j) * RPI;        // first key of this instruction
-                const int kcl = min(krow, S - 1);
-                const int pid = page_row[kcl >> p.page_shift];
-                const uint16_t *base = fetch_k + (size_t)pid * p.k_stride_page +
-                                       (size_t)(kcl & ((1 << p.page_shift) - 1)) * k_stride_s;
-                const int rows = live ? min(max(S - krow, 0), RPI) : 0;
-                const unsigned bytes = rows ? (unsigned)(rows - 1) * k_row_bytes + (unsigned)(D * 2) : 0u;
+                const uint16_t *base = fetch_k + page_off[c][j];
+                // (written so that it stays in scalar registers: a clamp on both sides is selected as a
+                // vector instruction, which would make the descriptor a per-lane value)
+                const bool on = live && krow < S;
+                const unsigned rows = min((unsigned)(S - krow), (unsigned)RPI);
+                const unsigned bytes = (unsigned)__builtin_amdgcn_readfirstlane(
+                    on ? (int)((rows - 1u) * k_row_bytes + (unsigned)(D * 2)) : 0);
                 const __amdgpu_buffer_rsrc_t rsrc =
                     __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
@@ -381,6 +402,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
             if (l + 1 == L) {
                 k_tile_off += k_tile_step;
                 k_dense = Kg;
+                if (has_next) load_pages(fetch_key0);
             } else {
                 k_dense += p.k_stride_l;
             }
