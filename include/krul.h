@@ -168,6 +168,8 @@ int krul_pair_similarity_strided(const krul_shape_t *shape, const void *q, const
  *                head_dim (else KRUL_EINVAL); for bf16 / f16 with head_dim 64 or 128, k_stride_s must be a multiple
  *                of head_dim below 2^27 (else KRUL_EUNSUPPORTED).  E.g. a [num_blocks][block_size][Hkv][d] pool:
  *                (block_size*Hkv*d, d, Hkv*d).
+ * Every page has room for block_size keys; the slots past the last key of a conversation may be read (their
+ * contents do not matter, NaN included).
  * Tables and pools are read by the kernels: they must stay valid and unchanged until the call's work on the
  * stream has finished; the caller guarantees that every page index lies inside its pool.  Everything else is as
  * for krul_pair_similarity (same workspace size; KRUL_FLAG_CAUSAL is honoured).

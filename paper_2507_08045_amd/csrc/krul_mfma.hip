@@ -234,6 +234,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         }
     };
     load_pages(key_begin);
+    const unsigned page_copy_bytes = (unsigned)(RPI - 1) * k_row_bytes + (unsigned)(D * 2);
     auto issue_chunk = [&](int c, bool live) __attribute__((always_inline)) {
         unsigned char *dst = slot_ptr(c);
         const int key0 = fetch_key0 + c * C::CH;
@@ -243,12 +244,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
             for (int j = 0; j < NLD; ++j) {
                 const int krow = key0 + (wave_u * NLD + j) * RPI;        // first key of this instruction
                 const uint16_t *base = fetch_k + page_off[c][j];
-                // (written so that it stays in scalar registers: a clamp on both sides is selected as a
-                // vector instruction, which would make the descriptor a per-lane value)
-                const bool on = live && krow < S;
-                const unsigned rows = min((unsigned)(S - krow), (unsigned)RPI);
-                const unsigned bytes = (unsigned)__builtin_amdgcn_readfirstlane(
-                    on ? (int)((rows - 1u) * k_row_bytes + (unsigned)(D * 2)) : 0);
+                // All RPI keys or none: a page has room for all its keys, so the ones past the last key of
+                // the conversation can be read (they are masked like any key a row does not see), and the
+                // range needs no arithmetic.  (A clamp to the keys that exist would also be selected as a
+                // vector instruction, which makes the descriptor a per-lane value issued in a retry loop.)
+                const unsigned bytes = live && krow < S ? page_copy_bytes : 0u;
                 const __amdgpu_buffer_rsrc_t rsrc =
                     __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(

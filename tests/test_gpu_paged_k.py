@@ -69,7 +69,7 @@ def test_paged_matches_oracle(G, oracle, case):
     rho = rng.uniform(0.5, 0.95, size=(B, L - 1, Hkv))
     w = workloads.make(name, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, dtype=dtype, rho_k=rho, seed=97)
     q, k = G.to_device(w)
-    pools, table, keep = scatter_pages(k, block, layout, spare=5, rng=rng, fill=1.0e4)   # a read of a wrong page wrecks the softmax
+    pools, table, keep = scatter_pages(k, block, layout, spare=5, rng=rng, fill=float("nan"))   # a wrong page, or an unmasked key past the last, wrecks the result
     want = oracle.pair_similarity(w.q, w.k)
     dense = G.gpu_scores(q, k)
     for fl in (0, kr.KRUL_FLAG_SINGLE_SPLIT, kr.KRUL_FLAG_GENERIC_KERNEL):
@@ -91,7 +91,7 @@ def test_paged_causal(G, oracle):
     B, L, Hq, Hkv, d, S, Tq = 1, 4, 8, 2, 128, 600, 33
     w = workloads.make("paged-causal", B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, dtype="bf16", seed=99)
     q, k = G.to_device(w)
-    pools, table, keep = scatter_pages(k, 16, "pbhd", 3, np.random.default_rng(1), 1.0e4)
+    pools, table, keep = scatter_pages(k, 16, "pbhd", 3, np.random.default_rng(1), float("nan"))
     want = oracle.pair_similarity(w.q, w.k, causal=True)
     out = kr.pair_similarity_paged(q, pools, table, S, flags=kr.KRUL_FLAG_CAUSAL)
     torch.cuda.synchronize()
