@@ -50,7 +50,18 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
     long long n_wg, records, spill_records = 0;
     if (mfma) {
         int kt;
-        if (Rk <= 32) { y.variant = kMfmaSlim; y.wr = 1; y.wk = 8; y.rb = 1; kt = 512; }
+        if (Rk <= 32) {
+            // Up to 32 rows per kv head (decode steps): bound by the stream of keys.  Three shapes of the
+            // same 32-row tile, by how many 512-key workgroups the problem gives the 256 CUs: too few to
+            // fill them -> half the keys and half the waves per workgroup, two workgroups per CU (a step
+            // over 4096 tokens, one conversation: 41 % -> 53 % of 8 TB/s; 8192 tokens: 50 % -> 68 %);
+            // two or more rounds of them -> four waves with three chunks of keys in flight instead of
+            // eight waves with one (+2..4 %, +6 % at head_dim 64); in between, eight waves.
+            const long long wgs512 = B * Hkv * ((S + 511) / 512);
+            if (wgs512 < 256) { y.variant = kMfmaShort; y.wr = 1; y.wk = 4; y.rb = 1; kt = 256; }
+            else if (wgs512 >= 512) { y.variant = kMfmaDeep; y.wr = 1; y.wk = 4; y.rb = 1; kt = 512; }
+            else { y.variant = kMfmaSlim; y.wr = 1; y.wk = 8; y.rb = 1; kt = 512; }
+        }
         else if (Rk <= 64) { y.variant = kMfmaMid; y.wr = 2; y.wk = 4; y.rb = 1; kt = 512; }
         else { y.variant = kMfmaWide; y.wr = 4; y.wk = 2; y.rb = 1; kt = 256; }
         const long long r_wg = y.wr * y.rb * 32;

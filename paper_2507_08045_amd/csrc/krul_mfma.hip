@@ -643,6 +643,10 @@ typedef Cfg<128, 2, 4, 1, 4> Mid128;    //  64 x 512, 8 waves, ring 4 x 128 keys
 typedef Cfg<64, 2, 4, 1, 4> Mid64;
 typedef Cfg<128, 1, 8, 1, 2> Slim128;   //  32 x 512, 8 waves, ring 2 x 256 keys (128 KB)
 typedef Cfg<64, 1, 8, 1, 2> Slim64;
+typedef Cfg<128, 1, 4, 1, 4> Deep128;   //  32 x 512, 4 waves, ring 4 x 128 keys (128 KB): three chunks in flight
+typedef Cfg<64, 1, 4, 1, 4> Deep64;
+typedef Cfg<128, 1, 4, 1, 2> Short128;  //  32 x 256, 4 waves, ring 2 x 128 keys ( 64 KB): two workgroups per CU
+typedef Cfg<64, 1, 4, 1, 2> Short64;
 
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
 {
@@ -654,6 +658,10 @@ hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
         return d128 ? launch_cfg<Mid128>(p, n_workgroups, st) : launch_cfg<Mid64>(p, n_workgroups, st);
     case kMfmaSlim:
         return d128 ? launch_cfg<Slim128>(p, n_workgroups, st) : launch_cfg<Slim64>(p, n_workgroups, st);
+    case kMfmaShort:
+        return d128 ? launch_cfg<Short128>(p, n_workgroups, st) : launch_cfg<Short64>(p, n_workgroups, st);
+    case kMfmaDeep:
+        return d128 ? launch_cfg<Deep128>(p, n_workgroups, st) : launch_cfg<Deep64>(p, n_workgroups, st);
     default:
         return hipErrorInvalidValue;
     }
