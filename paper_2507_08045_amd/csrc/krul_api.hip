@@ -50,32 +50,40 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
     long long n_wg, records, spill_records = 0;
     if (mfma) {
         int kt;
+        // Which shape of workgroup tile (rows x keys).  A shape's ordinary form is for problems that give
+        // the 256 CUs about a round of workgroups (w below) or more; with fewer, a "short" form with fewer
+        // keys per tile makes two to four times as many workgroups (measured, one conversation of
+        // Llama-3-8B shape: 64 query tokens over 2048 keys 92 -> 64 us, 16 over 4096 96 -> 63 us, one over
+        // 4096 82 -> 64 us).  The thresholds are where the two forms measured equal.
         if (Rk <= 32) {
-            // Up to 32 rows per kv head (decode steps): bound by the stream of keys.  Three shapes of the
-            // same 32-row tile, by how many 512-key workgroups the problem gives the 256 CUs: too few to
-            // fill them -> half the keys and half the waves per workgroup, two workgroups per CU (a step
-            // over 4096 tokens, one conversation: 41 % -> 53 % of 8 TB/s; 8192 tokens: 50 % -> 68 %);
-            // two or more rounds of them -> four waves with three chunks of keys in flight instead of
-            // eight waves with one (+2..4 %, +6 % at head_dim 64); in between, eight waves.
-            const long long wgs512 = B * Hkv * ((S + 511) / 512);
-            if (wgs512 < 256) { y.variant = kMfmaShort; y.wr = 1; y.wk = 4; y.rb = 1; kt = 256; }
-            else if (wgs512 >= 512) { y.variant = kMfmaDeep; y.wr = 1; y.wk = 4; y.rb = 1; kt = 512; }
+            // Decode steps, bound by the stream of keys.  With two or more rounds of workgroups, four waves
+            // with three chunks of keys in flight do better than eight waves with one (+2..4 %, +6 % at
+            // head_dim 64).
+            const long long w = B * Hkv * ((S + 511) / 512);
+            if (w <= 192) { y.variant = kMfmaSlimShort; y.wr = 1; y.wk = 4; y.rb = 1; kt = 256; }
+            else if (w >= 512) { y.variant = kMfmaSlimDeep; y.wr = 1; y.wk = 4; y.rb = 1; kt = 512; }
             else { y.variant = kMfmaSlim; y.wr = 1; y.wk = 8; y.rb = 1; kt = 512; }
+        } else if (Rk <= 64) {
+            const long long w = B * Hkv * ((S + 511) / 512);
+            if (w <= 128) { y.variant = kMfmaMidShort; y.wr = 2; y.wk = 2; y.rb = 1; kt = 128; }
+            else { y.variant = kMfmaMid; y.wr = 2; y.wk = 4; y.rb = 1; kt = 512; }
+        } else {
+            const long long w = B * Hkv * ((Rk + 127) / 128) * ((S + 255) / 256);
+            if (w <= 128) { y.variant = kMfmaWideShort; y.wr = 4; y.wk = 2; y.rb = 1; kt = 128; }
+            else { y.variant = kMfmaWide; y.wr = 4; y.wk = 2; y.rb = 1; kt = 256; }
         }
-        else if (Rk <= 64) { y.variant = kMfmaMid; y.wr = 2; y.wk = 4; y.rb = 1; kt = 512; }
-        else { y.variant = kMfmaWide; y.wr = 4; y.wk = 2; y.rb = 1; kt = 256; }
         const long long r_wg = y.wr * y.rb * 32;
         const long long nrt = (Rk + r_wg - 1) / r_wg;
         const long long units = B * Hkv * nrt;
         const long long tiles = (S + kt - 1) / kt;
         // the wide tile's workgroups are resident one per CU: aim for one round of them
-        const long long target = y.variant == kMfmaWide ? kTargetWorkgroups / 2 : kTargetWorkgroups;
+        const long long target = (y.variant == kMfmaWide || y.variant == kMfmaWideShort) ? kTargetWorkgroups / 2 : kTargetWorkgroups;
         long long want = (target + units - 1) / units;
         // The narrow tiles are bound by the stream of keys: there a split of several tiles, which
         // parks its running records in memory between tiles, costs a quarter of the bandwidth (a decode
         // step over 131072 tokens: 57 % of 8 TB/s against 74 % with one tile per split), and the
         // partial records stay below 1 % of the key bytes.  So: one tile per split, up to 1024 splits.
-        if (y.variant != kMfmaWide && want < 1024) want = 1024;
+        if (y.variant != kMfmaWide && y.variant != kMfmaWideShort && want < 1024) want = 1024;
         if (want < 1 || (s->flags & KRUL_FLAG_SINGLE_SPLIT)) want = 1;
         long long nsplit = want < tiles ? want : tiles;
         const long long tps = (tiles + nsplit - 1) / nsplit;

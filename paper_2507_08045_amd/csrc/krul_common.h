@@ -34,8 +34,10 @@ enum Variant : int {
     kMfmaWide = 1,  // bf16 MFMA, 128 rows x 256 keys per workgroup tile (4x2 waves)
     kMfmaMid = 2,   // bf16 MFMA,  64 rows x 512 keys per workgroup tile (2x4 waves)
     kMfmaSlim = 3,  // bf16 MFMA,  32 rows x 512 keys per workgroup tile (1x8 waves)
-    kMfmaDeep = 4,  // bf16 MFMA,  32 rows x 512 keys per workgroup tile (1x4 waves, three chunks in flight)
-    kMfmaShort = 5, // bf16 MFMA,  32 rows x 256 keys per workgroup tile (1x4 waves, two workgroups per CU)
+    kMfmaSlimDeep = 4,   // bf16 MFMA,  32 rows x 512 keys (1x4 waves, three chunks of keys in flight)
+    kMfmaSlimShort = 5,  // bf16 MFMA,  32 rows x 256 keys (1x4 waves, two workgroups per CU)
+    kMfmaMidShort = 6,   // bf16 MFMA,  64 rows x 128 keys (2x2 waves)
+    kMfmaWideShort = 7,  // bf16 MFMA, 128 rows x 128 keys (4x2 waves)
 };
 
 // How the state records of one launch are laid out; used by the producer kernels

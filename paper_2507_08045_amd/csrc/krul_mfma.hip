@@ -641,12 +641,16 @@ typedef Cfg<128, 4, 2, 1, 4> Wide128;   // 128 x 256, 8 waves, ring 4 x  64 keys
 typedef Cfg<64, 4, 2, 1, 4> Wide64;
 typedef Cfg<128, 2, 4, 1, 4> Mid128;    //  64 x 512, 8 waves, ring 4 x 128 keys (128 KB)
 typedef Cfg<64, 2, 4, 1, 4> Mid64;
+typedef Cfg<128, 4, 2, 1, 2> WideShort128;  // 128 x 128, 8 waves, ring 2 x  64 keys ( 32 KB): problems too small to fill the chip
+typedef Cfg<64, 4, 2, 1, 2> WideShort64;
+typedef Cfg<128, 2, 2, 1, 2> MidShort128;   //  64 x 128, 4 waves, ring 2 x  64 keys ( 32 KB): the same
+typedef Cfg<64, 2, 2, 1, 2> MidShort64;
 typedef Cfg<128, 1, 8, 1, 2> Slim128;   //  32 x 512, 8 waves, ring 2 x 256 keys (128 KB)
 typedef Cfg<64, 1, 8, 1, 2> Slim64;
-typedef Cfg<128, 1, 4, 1, 4> Deep128;   //  32 x 512, 4 waves, ring 4 x 128 keys (128 KB): three chunks in flight
-typedef Cfg<64, 1, 4, 1, 4> Deep64;
-typedef Cfg<128, 1, 4, 1, 2> Short128;  //  32 x 256, 4 waves, ring 2 x 128 keys ( 64 KB): two workgroups per CU
-typedef Cfg<64, 1, 4, 1, 2> Short64;
+typedef Cfg<128, 1, 4, 1, 4> SlimDeep128;   //  32 x 512, 4 waves, ring 4 x 128 keys (128 KB): three chunks in flight
+typedef Cfg<64, 1, 4, 1, 4> SlimDeep64;
+typedef Cfg<128, 1, 4, 1, 2> SlimShort128;  //  32 x 256, 4 waves, ring 2 x 128 keys ( 64 KB): two workgroups per CU
+typedef Cfg<64, 1, 4, 1, 2> SlimShort64;
 
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
 {
@@ -658,10 +662,14 @@ hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
         return d128 ? launch_cfg<Mid128>(p, n_workgroups, st) : launch_cfg<Mid64>(p, n_workgroups, st);
     case kMfmaSlim:
         return d128 ? launch_cfg<Slim128>(p, n_workgroups, st) : launch_cfg<Slim64>(p, n_workgroups, st);
-    case kMfmaShort:
-        return d128 ? launch_cfg<Short128>(p, n_workgroups, st) : launch_cfg<Short64>(p, n_workgroups, st);
-    case kMfmaDeep:
-        return d128 ? launch_cfg<Deep128>(p, n_workgroups, st) : launch_cfg<Deep64>(p, n_workgroups, st);
+    case kMfmaMidShort:
+        return d128 ? launch_cfg<MidShort128>(p, n_workgroups, st) : launch_cfg<MidShort64>(p, n_workgroups, st);
+    case kMfmaWideShort:
+        return d128 ? launch_cfg<WideShort128>(p, n_workgroups, st) : launch_cfg<WideShort64>(p, n_workgroups, st);
+    case kMfmaSlimShort:
+        return d128 ? launch_cfg<SlimShort128>(p, n_workgroups, st) : launch_cfg<SlimShort64>(p, n_workgroups, st);
+    case kMfmaSlimDeep:
+        return d128 ? launch_cfg<SlimDeep128>(p, n_workgroups, st) : launch_cfg<SlimDeep64>(p, n_workgroups, st);
     default:
         return hipErrorInvalidValue;
     }
