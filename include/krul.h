@@ -210,6 +210,29 @@ int krul_pair_scores_from_sums(const float *head_sum, const float *head_dist_sum
                                float *pair_score, float *head_score, float *pair_dist, void *stream);
 
 /*
+ * The accumulating call and the Initial-Recent call on keys read where a serving engine keeps them -- the
+ * token-wise scoring of Sec. 5 as it would run beside decoding: one call per decode step or prefill chunk,
+ * on the live cache.  keys names the source: exactly one of its members is set (else KRUL_EINVAL).
+ *   dense    as krul_pair_similarity takes them
+ *   strided  as for krul_pair_similarity_strided
+ *   paged    as for krul_pair_similarity_paged
+ * Everything else is as for krul_pair_similarity_accumulate and krul_pair_similarity_ir (same workspace
+ * sizes); the Initial-Recent regions are positions of the conversation, wherever its keys lie.
+ */
+typedef struct {
+    const void *dense;
+    const krul_k_layout_t *strided;
+    const krul_k_pages_t *paged;
+} krul_keys_t;
+int krul_pair_similarity_accumulate_in_place(const krul_shape_t *shape, const void *q, const krul_keys_t *keys,
+                                             float *head_sum, float *head_dist_sum,
+                                             void *workspace, size_t workspace_bytes, void *stream);
+int krul_pair_similarity_ir_in_place(const krul_shape_t *shape, const void *q, const krul_keys_t *keys, float gamma,
+                                     float *pair_score, float *head_score, float *pair_dist,
+                                     float *ir_mass, uint8_t *eligible,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * krul_pair_similarity with two caller-created HIP events (hipEvent_t passed as void*,
  * either may be NULL) recorded on the stream immediately before and after the
  * similarity kernel -- the kernel that forms the logits and the softmax sums and

@@ -45,6 +45,10 @@ class KrulKPages(ctypes.Structure):
                 ("k_stride_s", ctypes.c_int64)]
 
 
+class KrulKeys(ctypes.Structure):
+    _fields_ = [("dense", ctypes.c_void_p), ("strided", ctypes.POINTER(KrulKLayout)), ("paged", ctypes.POINTER(KrulKPages))]
+
+
 class KrulError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
@@ -84,6 +88,12 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_select.restype = ctypes.c_int
         L.krul_pair_similarity_select.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, ctypes.c_int32, vp, vp, vp,
                                                   vp, vp, vp, sz, vp, vp, vp]
+        L.krul_pair_similarity_accumulate_in_place.restype = ctypes.c_int
+        L.krul_pair_similarity_accumulate_in_place.argtypes = [ctypes.POINTER(KrulShape), vp, ctypes.POINTER(KrulKeys),
+                                                               vp, vp, vp, sz, vp]
+        L.krul_pair_similarity_ir_in_place.restype = ctypes.c_int
+        L.krul_pair_similarity_ir_in_place.argtypes = [ctypes.POINTER(KrulShape), vp, ctypes.POINTER(KrulKeys),
+                                                       ctypes.c_float, vp, vp, vp, vp, vp, vp, sz, vp]
         L.krul_pair_similarity_accumulate.restype = ctypes.c_int
         L.krul_pair_similarity_accumulate.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, sz, vp]
         L.krul_pair_scores_from_sums.restype = ctypes.c_int
@@ -323,6 +333,102 @@ def pair_similarity_accumulate(q: torch.Tensor, k: torch.Tensor, head_sum: torch
     if rc != KRUL_OK:
         raise KrulError(rc)
     return workspace
+
+
+class StridedKeys:
+    """Keys in one GPU tensor per layer, each indexed [B, Hkv, S, d] (see pair_similarity_strided)."""
+
+    def __init__(self, k_layers):
+        self.k_layers = list(k_layers)
+        self.table = None
+
+
+class PagedKeys:
+    """Keys in one pool of pages per layer and a block table (see pair_similarity_paged); n_hist keys per
+    conversation."""
+
+    def __init__(self, pools, block_table: torch.Tensor, n_hist: int):
+        self.pools, self.block_table, self.n_hist = list(pools), block_table, int(n_hist)
+        self.table = None
+
+
+def _keys(q: torch.Tensor, keys, scale: float, flags: int):
+    """(shape, KrulKeys, objects to keep alive) for dense keys (a tensor), StridedKeys or PagedKeys."""
+    if not q.is_cuda or q.dim() != 5 or not q.is_contiguous() or q.dtype not in _DTYPES:
+        raise ValueError("q must be a contiguous GPU tensor [B,L,Hq,Tq,d] of dtype float32, bfloat16 or float16")
+    B, L, Hq, Tq, d = q.shape
+    if isinstance(keys, torch.Tensor):
+        if not keys.is_cuda or not keys.is_contiguous():
+            raise ValueError("k must be a contiguous GPU tensor")
+        return make_shape(q, keys, scale, flags), KrulKeys(keys.data_ptr(), None, None), (keys,)
+    layers = keys.k_layers if isinstance(keys, StridedKeys) else keys.pools
+    t0 = layers[0]
+    if len(layers) != L or any(not t.is_cuda or t.dim() != 4 or t.shape != t0.shape or t.stride() != t0.stride()
+                               or t.dtype != q.dtype for t in layers) or t0.stride(3) != 1 or t0.shape[3] != d:
+        raise ValueError("one 4-d GPU tensor per layer, all of one shape, one set of strides, q's dtype and head_dim")
+    if keys.table is None:
+        keys.table = torch.tensor([t.data_ptr() for t in layers], dtype=torch.int64).to(q.device)
+    if isinstance(keys, StridedKeys):
+        if t0.shape[0] != B:
+            raise ValueError("q and k disagree on the batch")
+        shp = KrulShape(B, L, Hq, t0.shape[1], d, t0.shape[2], Tq, _DTYPES[q.dtype], float(scale), int(flags))
+        lay = KrulKLayout(keys.table.data_ptr(), t0.stride(0) if B > 1 else 0, t0.stride(1), t0.stride(2))
+        return shp, KrulKeys(None, ctypes.pointer(lay), None), (lay, keys)
+    bt = keys.block_table
+    if not bt.is_cuda or bt.dtype != torch.int32 or bt.dim() != 2 or not bt.is_contiguous() or bt.shape[0] != B:
+        raise ValueError("block_table must be a contiguous int32 GPU tensor [B, max_blocks]")
+    shp = KrulShape(B, L, Hq, t0.shape[2], d, keys.n_hist, Tq, _DTYPES[q.dtype], float(scale), int(flags))
+    pages = KrulKPages(keys.table.data_ptr(), bt.data_ptr(), t0.shape[1], bt.shape[1], t0.stride(0), t0.stride(2),
+                       t0.stride(1))
+    return shp, KrulKeys(None, None, ctypes.pointer(pages)), (pages, keys)
+
+
+def pair_similarity_accumulate_in_place(q: torch.Tensor, keys, head_sum: torch.Tensor,
+                                        head_dist_sum: torch.Tensor | None = None, *, scale: float = 0.0,
+                                        flags: int = 0, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """krul_pair_similarity_accumulate_in_place on the current stream; keys: a dense tensor, StridedKeys or
+    PagedKeys.  Returns the workspace."""
+    shp, ks, keep = _keys(q, keys, scale, flags)
+    want = (shp.batch, shp.n_layers - 1, shp.n_q_heads)
+    for t in (head_sum, head_dist_sum):
+        if t is not None and (not t.is_cuda or t.dtype != torch.float32 or tuple(t.shape) != want
+                              or not t.is_contiguous()):
+            raise ValueError("the running sums must be contiguous float32 GPU tensors [B, L-1, Hq]")
+    need = workspace_bytes(shp)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = lib().krul_pair_similarity_accumulate_in_place(
+        ctypes.byref(shp), _dev_ptr(q), ctypes.byref(ks), _dev_ptr(head_sum), _dev_ptr(head_dist_sum),
+        _dev_ptr(workspace), workspace.numel() if workspace is not None else 0, ctypes.c_void_p(_stream_ptr()))
+    del keep
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return workspace
+
+
+def pair_similarity_ir_in_place(q: torch.Tensor, keys, gamma: float, *, scale: float = 0.0, flags: int = 0,
+                                want_head_score: bool = True, want_pair_dist: bool = True,
+                                workspace: torch.Tensor | None = None) -> dict:
+    """krul_pair_similarity_ir_in_place on the current stream; keys: a dense tensor, StridedKeys or PagedKeys."""
+    shp, ks, keep = _keys(q, keys, scale, flags)
+    need = workspace_bytes_ir(shp)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    B, L, Hq = shp.batch, shp.n_layers, shp.n_q_heads
+    ps = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
+    hs = torch.empty((B, L - 1, Hq), dtype=torch.float32, device=q.device) if want_head_score else None
+    pd = torch.empty((B, L - 1), dtype=torch.float32, device=q.device) if want_pair_dist else None
+    mass = torch.empty((B, L), dtype=torch.float32, device=q.device)
+    el = torch.empty((B, L), dtype=torch.uint8, device=q.device)
+    rc = lib().krul_pair_similarity_ir_in_place(
+        ctypes.byref(shp), _dev_ptr(q), ctypes.byref(ks), float(gamma), _dev_ptr(ps), _dev_ptr(hs), _dev_ptr(pd),
+        _dev_ptr(mass), _dev_ptr(el), _dev_ptr(workspace), workspace.numel() if workspace is not None else 0,
+        ctypes.c_void_p(_stream_ptr()))
+    del keep
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "ir_mass": mass, "eligible": el,
+            "workspace": workspace}
 
 
 def pair_scores_from_sums(head_sum: torch.Tensor, n_tokens: float, head_dist_sum: torch.Tensor | None = None) -> dict:

@@ -390,6 +390,33 @@ int krul_pair_similarity_accumulate(const krul_shape_t *shape, const void *q, co
                           workspace, workspace_bytes, stream, nullptr, nullptr, true);
 }
 
+namespace {
+// exactly one source of keys
+bool one_source(const krul_keys_t *keys)
+{
+    return keys && (keys->dense != nullptr) + (keys->strided != nullptr) + (keys->paged != nullptr) == 1;
+}
+}  // namespace
+
+int krul_pair_similarity_accumulate_in_place(const krul_shape_t *shape, const void *q, const krul_keys_t *keys,
+                                             float *head_sum, float *head_dist_sum,
+                                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!one_source(keys)) return KRUL_EINVAL;
+    return run_similarity(shape, q, keys->dense, nullptr, head_sum, head_dist_sum, false, 0.f, nullptr, nullptr,
+                          workspace, workspace_bytes, stream, nullptr, nullptr, true, keys->strided, keys->paged);
+}
+
+int krul_pair_similarity_ir_in_place(const krul_shape_t *shape, const void *q, const krul_keys_t *keys, float gamma,
+                                     float *pair_score, float *head_score, float *pair_dist,
+                                     float *ir_mass, uint8_t *eligible,
+                                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!one_source(keys)) return KRUL_EINVAL;
+    return run_similarity(shape, q, keys->dense, pair_score, head_score, pair_dist, true, gamma, ir_mass, eligible,
+                          workspace, workspace_bytes, stream, nullptr, nullptr, false, keys->strided, keys->paged);
+}
+
 int krul_pair_scores_from_sums(const float *head_sum, const float *head_dist_sum,
                                int32_t batch, int32_t n_layers, int32_t n_q_heads, float n_tokens,
                                float *pair_score, float *head_score, float *pair_dist, void *stream)
