@@ -231,6 +231,10 @@ int krul_pair_similarity_ir_in_place(const krul_shape_t *shape, const void *q, c
                                      float *pair_score, float *head_score, float *pair_dist,
                                      float *ir_mass, uint8_t *eligible,
                                      void *workspace, size_t workspace_bytes, void *stream);
+/* ... and krul_all_pairs_similarity (declared below; same outputs, workspace and limits) on such keys. */
+int krul_all_pairs_similarity_in_place(const krul_shape_t *shape, const void *q, const krul_keys_t *keys,
+                                       float *pair_score_all, float *pair_dist_all, float *head_score_all,
+                                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * krul_pair_similarity with two caller-created HIP events (hipEvent_t passed as void*,

@@ -91,6 +91,9 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_accumulate_in_place.restype = ctypes.c_int
         L.krul_pair_similarity_accumulate_in_place.argtypes = [ctypes.POINTER(KrulShape), vp, ctypes.POINTER(KrulKeys),
                                                                vp, vp, vp, sz, vp]
+        L.krul_all_pairs_similarity_in_place.restype = ctypes.c_int
+        L.krul_all_pairs_similarity_in_place.argtypes = [ctypes.POINTER(KrulShape), vp, ctypes.POINTER(KrulKeys),
+                                                         vp, vp, vp, vp, sz, vp]
         L.krul_pair_similarity_ir_in_place.restype = ctypes.c_int
         L.krul_pair_similarity_ir_in_place.argtypes = [ctypes.POINTER(KrulShape), vp, ctypes.POINTER(KrulKeys),
                                                        ctypes.c_float, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -539,6 +542,31 @@ def all_pairs_similarity(q: torch.Tensor, k: torch.Tensor, *, scale: float = 0.0
     rc = lib().krul_all_pairs_similarity(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), _dev_ptr(ps), _dev_ptr(pd),
                                          _dev_ptr(hs), _dev_ptr(workspace), workspace.numel(),
                                          ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return {"pair_score": ps, "pair_dist": pd, "head_score": hs, "workspace": workspace}
+
+
+def all_pairs_similarity_in_place(q: torch.Tensor, keys, *, scale: float = 0.0, flags: int = 0,
+                                  want_pair_dist: bool = True, want_head_score: bool = False,
+                                  workspace: torch.Tensor | None = None, max_workspace_bytes: int = 0) -> dict:
+    """krul_all_pairs_similarity_in_place on the current stream; keys: a dense tensor, StridedKeys or PagedKeys."""
+    shp, ks, keep = _keys(q, keys, scale, flags)
+    B, L, Hq = shp.batch, shp.n_layers, shp.n_q_heads
+    if workspace is None:
+        need = all_pairs_workspace_bytes(shp, max_workspace_bytes)
+        if need == 0:   # let the library name the reason
+            rc = lib().krul_all_pairs_similarity_in_place(ctypes.byref(shp), _dev_ptr(q), ctypes.byref(ks), None, None,
+                                                          None, None, 0, None)
+            raise KrulError(rc if rc != 0 else KRUL_EINVAL)
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ps = torch.empty((B, L, L), dtype=torch.float32, device=q.device)
+    pd = torch.empty((B, L, L), dtype=torch.float32, device=q.device) if want_pair_dist else None
+    hs = torch.empty((B, Hq, L, L), dtype=torch.float32, device=q.device) if want_head_score else None
+    rc = lib().krul_all_pairs_similarity_in_place(ctypes.byref(shp), _dev_ptr(q), ctypes.byref(ks), _dev_ptr(ps),
+                                                  _dev_ptr(pd), _dev_ptr(hs), _dev_ptr(workspace), workspace.numel(),
+                                                  ctypes.c_void_p(_stream_ptr()))
+    del keep
     if rc != KRUL_OK:
         raise KrulError(rc)
     return {"pair_score": ps, "pair_dist": pd, "head_score": hs, "workspace": workspace}

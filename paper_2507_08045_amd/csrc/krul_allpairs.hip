@@ -57,6 +57,7 @@ struct APParams {
     const void *k;
     int B, L, Hq, Hkv, g, d, S, Tq, Rk;
     int causal;
+    KeyAddr ka;         // where the keys are (dense: ka.k; in place: per-layer table, strides, pages)
     float c;            // scale * log2(e)
     int NW;             // 32-row blocks per row group (1, 2, 4 or 8: the waves of a weights-kernel workgroup
                         // times the blocks each takes)
@@ -101,7 +102,9 @@ __device__ inline uint32_t pack_f16(float a, float b)
 // 1. weights kernel (bf16, head_dim 64 or 128)
 // NW waves, each with RB 32-row blocks (taken one after the other against the same keys in LDS): a
 // row group is NW*RB blocks.
-template <int D, int NW, int RB, bool F16>
+// INPLACE: the keys are read where the caller keeps them (one allocation or page pool per layer, strides,
+// a block table) instead of from the dense layout.
+template <int D, int NW, int RB, bool F16, bool INPLACE>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kernel(APParams p)
 {
     constexpr int KS = D / 16, ROWB = D * 2, KR = kKeysPerSplit, NKBW = KR / 32;
@@ -133,7 +136,15 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
     // This workgroup walks the key splits [t0, t1) of its rows and layer, KR keys each.  The keys of
     // split t+1 are copied into the other LDS buffer while split t is worked on.
     const int t0 = kc * p.tpw, t1 = min(p.nsplit, t0 + p.tpw);
-    [[maybe_unused]] const uint16_t *klayer = static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S) * D;
+    // dense: this unit's keys of layer l; in place: the layer's allocation at this unit's kv head (and
+    // conversation, unless a block table says where its keys are)
+    typedef const __attribute__((address_space(4))) unsigned long long *const_u64_ptr;   // constant memory: scalar loads
+    typedef const __attribute__((address_space(4))) int *const_i32_ptr;
+    [[maybe_unused]] const uint16_t *klayer =
+        INPLACE ? (const uint16_t *)(uintptr_t)((const_u64_ptr)(uintptr_t)p.ka.k_tab)[l] + (size_t)kvh * p.ka.stride_h +
+                      (p.ka.block_table ? 0 : (size_t)b * p.ka.stride_b)
+                : static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S) * D;
+    [[maybe_unused]] const unsigned k_row_bytes = INPLACE ? (unsigned)p.ka.stride_s * 2u : (unsigned)ROWB;
     // The keys go HBM -> LDS directly (buffer_load ... lds, no staging registers):
     // wave-instruction j fills the 1 KB at j*1024 (RPI key rows), lane by lane, so each lane fetches
     // the 16-byte piece that belongs at its LDS position (the XOR swizzle applied on the global
@@ -142,6 +153,45 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
 #if defined(__HIP_DEVICE_COMPILE__)   // (the host pass only needs the kernel's launch stub)
         constexpr int RPI = 64 / PPR, NI = KR / RPI / NW;
         const int kn = min(KR, S - t * KR);
+        if constexpr (INPLACE) {
+            if (p.ka.block_table) {
+                // pages: a copy instruction's RPI keys lie in one page (pages hold a power of two >= 8 keys);
+                // it looks its page up (scalar load) and gets a descriptor of its own: all its keys or none
+                // (a page has room for all its keys; the ones past the last are masked like any unseen key)
+                const const_i32_ptr page_row = (const_i32_ptr)(uintptr_t)(p.ka.block_table + (size_t)b * p.ka.max_blocks);
+#pragma unroll
+                for (int jj = 0; jj < NI; ++jj) {
+                    const int j = __builtin_amdgcn_readfirstlane(w) * NI + jj;
+                    const int krow = t * KR + j * RPI, kcl = min(krow, S - 1);
+                    const uint16_t *base = klayer + (size_t)page_row[kcl >> p.ka.page_shift] * p.ka.stride_page +
+                                           (size_t)(kcl & ((1 << p.ka.page_shift) - 1)) * p.ka.stride_s;
+                    const unsigned bytes = krow < S ? (unsigned)(RPI - 1) * k_row_bytes + (unsigned)ROWB : 0u;
+                    const __amdgpu_buffer_rsrc_t rsrc =
+                        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
+                    const int row = j * RPI + lane / PPR, pos = lane % PPR;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        rsrc, (__attribute__((address_space(3))) void *)(&kl[buf][0] + j * 1024), 16,
+                        (int)((unsigned)(lane / PPR) * k_row_bytes + (unsigned)((pos ^ swz<D>(row)) << 4)), 0, 0, 0);
+                }
+            } else {
+                // strides: one descriptor for the split, the row pitch a run-time value
+                const uintptr_t ka = (uintptr_t)(klayer + (size_t)t * KR * p.ka.stride_s);
+                const uint16_t *kb_u = (const uint16_t *)(((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(ka >> 32)) << 32) |
+                                                          (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)ka));
+                const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<uint16_t *>(kb_u), 0,
+                    __builtin_amdgcn_readfirstlane(kn > 0 ? (int)((unsigned)(kn - 1) * k_row_bytes + (unsigned)ROWB) : 0), 0x00020000);
+#pragma unroll
+                for (int jj = 0; jj < NI; ++jj) {
+                    const int j = __builtin_amdgcn_readfirstlane(w) * NI + jj;
+                    const int row = j * RPI + lane / PPR, pos = lane % PPR;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        rsrc, (__attribute__((address_space(3))) void *)(&kl[buf][0] + j * 1024), 16,
+                        (int)((unsigned)row * k_row_bytes + (unsigned)((pos ^ swz<D>(row)) << 4)), 0, 0, 0);
+                }
+            }
+            return;
+        }
         const uintptr_t ka = (uintptr_t)(klayer + (size_t)t * KR * D);   // wave-uniform: a scalar descriptor
         const uint16_t *kb_u = (const uint16_t *)(((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(ka >> 32)) << 32) |
                                                   (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)ka));
@@ -295,15 +345,21 @@ __global__ __launch_bounds__(64) void ap_weights_generic_kernel(APParams p)
     const int S = p.S, d = p.d;
     const int row_end = p.causal ? S - p.Tq + t + 1 : S;
     const T *Q = static_cast<const T *>(p.q);
-    const T *K = static_cast<const T *>(p.k);
+    const T *K = p.ka.k_tab ? static_cast<const T *>(p.ka.k_tab[l]) : static_cast<const T *>(p.ka.k) + (size_t)l * p.ka.stride_l;
     const size_t qoff = ((((size_t)b * p.L + l) * p.Hq + hq) * p.Tq + t) * d;
-    const size_t koff = ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S) * d;
+    auto key_off = [&](int key) -> size_t {   // (see KeyAddr)
+        if (p.ka.block_table)
+            return (size_t)p.ka.block_table[(size_t)b * p.ka.max_blocks + (key >> p.ka.page_shift)] * p.ka.stride_page +
+                   (size_t)kvh * p.ka.stride_h + (size_t)(key & ((1 << p.ka.page_shift) - 1)) * p.ka.stride_s;
+        return (size_t)b * p.ka.stride_b + (size_t)kvh * p.ka.stride_h + (size_t)key * p.ka.stride_s;
+    };
     for (int i = lane; i < d; i += 64) qs[i] = load_f32<T>(Q, qoff + i);
     __syncthreads();
 
     auto logit = [&](int key) -> float {
         float acc = 0.f;
-        for (int i = 0; i < d; ++i) acc = fmaf(qs[i], load_f32<T>(K, koff + (size_t)key * d + i), acc);
+        const size_t koff = key_off(key);
+        for (int i = 0; i < d; ++i) acc = fmaf(qs[i], load_f32<T>(K, koff + i), acc);
         return acc * p.c;
     };
     float mx = -INFINITY;
@@ -802,11 +858,20 @@ template <int D, bool F16>
 void launch_weights(const APParams &p, hipStream_t st)
 {
     const dim3 grid(p.nrg * p.L * ((p.nsplit + p.tpw - 1) / p.tpw));
+    if (p.ka.k_tab) {
+        switch (p.NW) {
+        case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1, 1, F16, true>), grid, dim3(64), 0, st, p); break;
+        case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2, 1, F16, true>), grid, dim3(128), 0, st, p); break;
+        case 4: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 1, F16, true>), grid, dim3(256), 0, st, p); break;
+        default: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 2, F16, true>), grid, dim3(256), 0, st, p); break;
+        }
+        return;
+    }
     switch (p.NW) {
-    case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1, 1, F16>), grid, dim3(64), 0, st, p); break;
-    case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2, 1, F16>), grid, dim3(128), 0, st, p); break;
-    case 4: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 1, F16>), grid, dim3(256), 0, st, p); break;
-    default: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 2, F16>), grid, dim3(256), 0, st, p); break;
+    case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1, 1, F16, false>), grid, dim3(64), 0, st, p); break;
+    case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2, 1, F16, false>), grid, dim3(128), 0, st, p); break;
+    case 4: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 1, F16, false>), grid, dim3(256), 0, st, p); break;
+    default: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 4, 2, F16, false>), grid, dim3(256), 0, st, p); break;
     }
 }
 
@@ -819,14 +884,15 @@ size_t all_pairs_workspace(const krul_shape_t *s, size_t max_bytes)
     return pl.total_bytes;
 }
 
-int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pair_score, float *pair_dist,
-                  float *head_score, void *workspace, size_t workspace_bytes, hipStream_t st)
+int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, const krul_k_layout_t *kl,
+                  const krul_k_pages_t *kp, float *pair_score, float *pair_dist, float *head_score,
+                  void *workspace, size_t workspace_bytes, hipStream_t st)
 {
     APPlan pl;
     int rc = ap_plan(s, 1, &pl);   // the smallest batch: one row group
     if (rc != KRUL_OK) return rc;
-    if (!q || !k || !pair_score) return KRUL_EINVAL;
-    if (((uintptr_t)q | (uintptr_t)k) & 15) return KRUL_EINVAL;
+    if (!q || !pair_score) return KRUL_EINVAL;
+    if ((uintptr_t)q & 15) return KRUL_EINVAL;
     if (((uintptr_t)pair_score | (uintptr_t)pair_dist | (uintptr_t)head_score) & 3) return KRUL_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pl.total_bytes) return KRUL_EWORKSPACE;
     // the batch is what the caller's workspace holds
@@ -838,6 +904,8 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pa
     APParams p;
     p.q = q;
     p.k = k;
+    rc = resolve_keys(s, pl.mfma, false, k, kl, kp, &p.ka);
+    if (rc != KRUL_OK) return rc;
     p.B = s->batch;
     p.L = s->n_layers;
     p.Hq = s->n_q_heads;

@@ -131,6 +131,55 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
     return KRUL_OK;
 }
 
+int resolve_keys(const krul_shape_t *s, bool mfma, bool dense_2gib, const void *k, const krul_k_layout_t *kl,
+                 const krul_k_pages_t *kp, KeyAddr *out)
+{
+    if ((k != nullptr) + (kl != nullptr) + (kp != nullptr) != 1) return KRUL_EINVAL;
+    const long long d = s->head_dim, S = s->n_hist;
+    KeyAddr a = {};
+    if (k) {
+        if ((uintptr_t)k & 15) return KRUL_EINVAL;
+        if (mfma && dense_2gib && S * d * 2 >= (1ll << 31)) return KRUL_EUNSUPPORTED;
+        a.k = k;
+        a.stride_l = (long long)s->n_kv_heads * S * d;
+        a.stride_b = (long long)s->n_layers * s->n_kv_heads * S * d;
+        a.stride_h = S * d;
+        a.stride_s = d;
+    } else if (kl) {
+        if (!kl->k_layers || ((uintptr_t)kl->k_layers & 7)) return KRUL_EINVAL;
+        const long long sb = s->batch > 1 ? kl->k_stride_b : 8;   // (not used for one conversation)
+        if (sb <= 0 || kl->k_stride_h <= 0 || kl->k_stride_s < d || ((sb | kl->k_stride_h | kl->k_stride_s) & 7))
+            return KRUL_EINVAL;
+        // the matrix-core kernels' row swizzle needs whole head_dim multiples between keys; 32-bit
+        // offsets and ranges need a layer's keys of one head to span less than 2 GiB
+        if (mfma && (kl->k_stride_s % d != 0 || kl->k_stride_s >= (1ll << 23) ||
+                     (dense_2gib && kl->k_stride_s * 2 * S >= (1ll << 31))))
+            return KRUL_EUNSUPPORTED;
+        a.k_tab = kl->k_layers;
+        a.stride_b = s->batch > 1 ? kl->k_stride_b : 0;
+        a.stride_h = kl->k_stride_h;
+        a.stride_s = kl->k_stride_s;
+    } else {
+        if (!kp->k_layers || !kp->block_table || ((uintptr_t)kp->k_layers & 7) || ((uintptr_t)kp->block_table & 3))
+            return KRUL_EINVAL;
+        const int bs = kp->block_size;
+        if (bs < 8 || (bs & (bs - 1)) || kp->max_blocks < (S + bs - 1) / bs || kp->k_stride_block <= 0 ||
+            kp->k_stride_h <= 0 || kp->k_stride_s < d || ((kp->k_stride_block | kp->k_stride_h | kp->k_stride_s) & 7))
+            return KRUL_EINVAL;
+        // (row swizzle; 32-bit byte offsets over the keys one copy instruction moves)
+        if (mfma && (kp->k_stride_s % d != 0 || kp->k_stride_s >= (1ll << 27))) return KRUL_EUNSUPPORTED;
+        a.k_tab = kp->k_layers;
+        a.block_table = kp->block_table;
+        a.max_blocks = kp->max_blocks;
+        for (a.page_shift = 3; (1 << a.page_shift) < bs; ++a.page_shift) {}
+        a.stride_page = kp->k_stride_block;
+        a.stride_h = kp->k_stride_h;
+        a.stride_s = kp->k_stride_s;
+    }
+    *out = a;
+    return KRUL_OK;
+}
+
 }  // namespace krul
 
 using namespace krul;
@@ -166,13 +215,9 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     Plan pl;
     const int rc = make_plan(shape, &pl, ir);
     if (rc != KRUL_OK) return rc;
-    if (!q || (kp ? (!kp->k_layers || !kp->block_table) : kl ? !kl->k_layers : !k) ||
-        (accumulate ? !head_score : !pair_score))
-        return KRUL_EINVAL;
+    if (!q || (accumulate ? !head_score : !pair_score)) return KRUL_EINVAL;
     if (ir && (shape->flags & KRUL_FLAG_CAUSAL)) return KRUL_EUNSUPPORTED;
-    if (((uintptr_t)q | (uintptr_t)k) & 15 || (kl && ((uintptr_t)kl->k_layers & 7)) ||
-        (kp && (((uintptr_t)kp->k_layers & 7) || ((uintptr_t)kp->block_table & 3))))
-        return KRUL_EINVAL;
+    if ((uintptr_t)q & 15) return KRUL_EINVAL;
     if (((uintptr_t)pair_score | (uintptr_t)head_score | (uintptr_t)pair_dist | (uintptr_t)ir_mass) & 3)
         return KRUL_EINVAL;
     if (ir && (!(gamma >= 0.f) || !isfinite(gamma) || (!ir_mass && !eligible))) return KRUL_EINVAL;
@@ -183,7 +228,6 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     SimParams p;
     p.q = q;
-    p.k = k;
     p.state = reinterpret_cast<float4 *>(ws);
     p.spill = reinterpret_cast<float4 *>(ws + pl.spill_off);
     p.B = shape->batch;
@@ -207,48 +251,19 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     p.spill_ir = reinterpret_cast<float *>(ws + pl.spill_ir_off);
     p.lay = pl.lay;
     {
-        const long long d = p.d, S = p.S;
-        p.k_tab = nullptr;
-        p.block_table = nullptr;
-        p.page_shift = p.max_blocks = 0;
-        p.k_stride_page = 0;
-        p.k_stride_l = (long long)p.Hkv * S * d;
-        p.k_stride_b = (long long)p.L * p.Hkv * S * d;
-        p.k_stride_h = S * d;
-        p.k_stride_s = d;
-        if (kl) {
-            const long long sb = p.B > 1 ? kl->k_stride_b : 8;   // (not used for one conversation)
-            if (sb <= 0 || kl->k_stride_h <= 0 || kl->k_stride_s < d || ((sb | kl->k_stride_h | kl->k_stride_s) & 7))
-                return KRUL_EINVAL;
-            // the MFMA kernel's row swizzle needs whole head_dim multiples between keys; its 32-bit
-            // offsets and ranges need a layer's keys of one head to span less than 2 GiB
-            if (pl.lay.variant != kGeneric &&
-                (kl->k_stride_s % d != 0 || kl->k_stride_s * 2 * S >= (1ll << 31)))
-                return KRUL_EUNSUPPORTED;
-            p.k_tab = kl->k_layers;
-            p.k_stride_l = 0;
-            p.k_stride_b = p.B > 1 ? kl->k_stride_b : 0;
-            p.k_stride_h = kl->k_stride_h;
-            p.k_stride_s = kl->k_stride_s;
-        } else if (kp) {
-            const int bs = kp->block_size;
-            if (bs < 8 || (bs & (bs - 1)) || kp->max_blocks < (S + bs - 1) / bs || kp->k_stride_block <= 0 ||
-                kp->k_stride_h <= 0 || kp->k_stride_s < d || ((kp->k_stride_block | kp->k_stride_h | kp->k_stride_s) & 7))
-                return KRUL_EINVAL;
-            // (row swizzle; 32-bit byte offsets over the keys one copy instruction moves)
-            if (pl.lay.variant != kGeneric && (kp->k_stride_s % d != 0 || kp->k_stride_s >= (1ll << 27)))
-                return KRUL_EUNSUPPORTED;
-            p.k_tab = kp->k_layers;
-            p.block_table = kp->block_table;
-            p.max_blocks = kp->max_blocks;
-            for (p.page_shift = 3; (1 << p.page_shift) < bs; ++p.page_shift) {}
-            p.k_stride_page = kp->k_stride_block;
-            p.k_stride_l = p.k_stride_b = 0;
-            p.k_stride_h = kp->k_stride_h;
-            p.k_stride_s = kp->k_stride_s;
-        } else if (pl.lay.variant != kGeneric && S * d * 2 >= (1ll << 31)) {
-            return KRUL_EUNSUPPORTED;
-        }
+        KeyAddr ka;
+        const int krc = resolve_keys(shape, pl.lay.variant != kGeneric, true, k, kl, kp, &ka);
+        if (krc != KRUL_OK) return krc;
+        p.k = ka.k;
+        p.k_tab = ka.k_tab;
+        p.k_stride_l = ka.stride_l;
+        p.k_stride_b = ka.stride_b;
+        p.k_stride_h = ka.stride_h;
+        p.k_stride_s = ka.stride_s;
+        p.block_table = ka.block_table;
+        p.page_shift = ka.page_shift;
+        p.max_blocks = ka.max_blocks;
+        p.k_stride_page = ka.stride_page;
     }
 
     if (event_begin && hipEventRecord(static_cast<hipEvent_t>(event_begin), st) != hipSuccess)
@@ -331,6 +346,23 @@ int krul_pair_similarity_strided(const krul_shape_t *shape, const void *q, const
                           workspace, workspace_bytes, stream, nullptr, nullptr, false, k_layout);
 }
 
+namespace {
+// exactly one source of keys
+bool one_source(const krul_keys_t *keys)
+{
+    return keys && (keys->dense != nullptr) + (keys->strided != nullptr) + (keys->paged != nullptr) == 1;
+}
+}  // namespace
+
+int krul_all_pairs_similarity_in_place(const krul_shape_t *shape, const void *q, const krul_keys_t *keys,
+                                       float *pair_score_all, float *pair_dist_all, float *head_score_all,
+                                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!one_source(keys)) return KRUL_EINVAL;
+    return run_all_pairs(shape, q, keys->dense, keys->strided, keys->paged, pair_score_all, pair_dist_all,
+                         head_score_all, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
 size_t krul_all_pairs_workspace(const krul_shape_t *shape, size_t max_bytes)
 {
     return all_pairs_workspace(shape, max_bytes);
@@ -340,8 +372,8 @@ int krul_all_pairs_similarity(const krul_shape_t *shape, const void *q, const vo
                               float *pair_score_all, float *pair_dist_all, float *head_score_all,
                               void *workspace, size_t workspace_bytes, void *stream)
 {
-    return run_all_pairs(shape, q, k, pair_score_all, pair_dist_all, head_score_all, workspace, workspace_bytes,
-                         static_cast<hipStream_t>(stream));
+    return run_all_pairs(shape, q, k, nullptr, nullptr, pair_score_all, pair_dist_all, head_score_all, workspace,
+                         workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 int krul_select_pairs_all(const float *score, int32_t closer_is_smaller, const uint8_t *eligible,
@@ -389,14 +421,6 @@ int krul_pair_similarity_accumulate(const krul_shape_t *shape, const void *q, co
     return run_similarity(shape, q, k, nullptr, head_sum, head_dist_sum, false, 0.f, nullptr, nullptr,
                           workspace, workspace_bytes, stream, nullptr, nullptr, true);
 }
-
-namespace {
-// exactly one source of keys
-bool one_source(const krul_keys_t *keys)
-{
-    return keys && (keys->dense != nullptr) + (keys->strided != nullptr) + (keys->paged != nullptr) == 1;
-}
-}  // namespace
 
 int krul_pair_similarity_accumulate_in_place(const krul_shape_t *shape, const void *q, const krul_keys_t *keys,
                                              float *head_sum, float *head_dist_sum,

@@ -112,12 +112,31 @@ constexpr int kPairsSelectMaxBatch = 16;
 // Host: shape checks common to all entry points.  Returns a krul_status_t.
 int check_shape(const krul_shape_t *s);
 
+// Where the keys are, in the kernels' terms (elements of the storage type): layer l starts at k_tab[l] if
+// k_tab is set (a device array of device pointers), else at k + l * stride_l; inside a layer the key
+// (b, kv head, j) starts at b * stride_b + kvh * stride_h + j * stride_s -- or, if block_table is set, at
+// block_table[b * max_blocks + (j >> page_shift)] * stride_page + kvh * stride_h + (j & (2^page_shift - 1)) * stride_s.
+struct KeyAddr {
+    const void *k;
+    const void *const *k_tab;
+    long long stride_l, stride_b, stride_h, stride_s;
+    const int *block_table;
+    int page_shift, max_blocks;
+    long long stride_page;
+};
+// Host: validate one source of keys (exactly one of k, kl, kp set) for a checked shape and put it in the
+// kernels' terms.  mfma: the matrix-core kernels will read it (their row swizzle and 32-bit offsets add
+// limits); dense_2gib: ... and address a layer's keys of one head with 32-bit offsets.  Returns a krul_status_t.
+int resolve_keys(const krul_shape_t *s, bool mfma, bool dense_2gib, const void *k, const krul_k_layout_t *kl,
+                 const krul_k_pages_t *kp, KeyAddr *out);
+
 // Similarity of every two layers (krul_allpairs.hip).  all_pairs_workspace: bytes for the largest batch
 // of rows that fits max_bytes (0: a default budget), 0 if the shape is not supported.  run_all_pairs
 // validates, enqueues everything on st and returns a krul_status_t.
 size_t all_pairs_workspace(const krul_shape_t *s, size_t max_bytes);
-int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, float *pair_score, float *pair_dist,
-                  float *head_score, void *workspace, size_t workspace_bytes, hipStream_t st);
+int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, const krul_k_layout_t *kl,
+                  const krul_k_pages_t *kp, float *pair_score, float *pair_dist, float *head_score,
+                  void *workspace, size_t workspace_bytes, hipStream_t st);
 hipError_t launch_select_all(const float *score, int closer_is_smaller, const uint8_t *eligible, int batch,
                              int n_layers, int n_select, int32_t *out_pairs, int32_t *out_count, hipStream_t st);
 

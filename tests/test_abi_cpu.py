@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(kr):
             "krul_pair_similarity_accumulate", "krul_pair_scores_from_sums",
             "krul_pair_similarity_strided", "krul_all_pairs_similarity", "krul_all_pairs_workspace",
             "krul_select_pairs_all", "krul_pair_similarity_paged", "krul_pair_similarity_select", "krul_pair_similarity_accumulate_in_place",
-            "krul_pair_similarity_ir_in_place"} <= set(names)
+            "krul_pair_similarity_ir_in_place", "krul_all_pairs_similarity_in_place"} <= set(names)
     lib = kr.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in krul.h but not exported"

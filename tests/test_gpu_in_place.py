@@ -81,6 +81,28 @@ def test_accumulate_and_ir_equal_the_dense_calls(G, oracle, dtype, d, flag):
     del keep
 
 
+@pytest.mark.parametrize("dtype,d,S,Tq,flag", [("bf16", 128, 700, 40, 0), ("f16", 64, 300, 5, 0), ("bf16", 128, 2080, 2, "causal"),
+                                              ("f32", 64, 256, 16, 0), ("bf16", 96, 200, 3, 0)])
+def test_all_pairs_in_place(G, oracle, dtype, d, S, Tq, flag):
+    """Every two layers scored on keys read in place: the same bits as the dense call, and the oracle's values."""
+    import paper_2507_08045_amd as kr
+    flags = kr.KRUL_FLAG_CAUSAL if flag == "causal" else 0
+    B, L, Hq, Hkv = 2, 6, 8, 2
+    w = workloads.make(f"ap-in-place-{dtype}-{d}", B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, dtype=dtype, seed=403)
+    q, k = G.to_device(w)
+    pools, table, keep = scatter_pages(k, 16, "pbhd", 3, np.random.default_rng(7), float("nan"))
+    ref = kr.all_pairs_similarity(q, k, flags=flags, want_head_score=True)
+    torch.cuda.synchronize()
+    want = oracle.all_pairs(w.q, w.k, causal=bool(flags))
+    G.assert_close(ref["head_score"].cpu().numpy(), want["head_score"], G.TOL, "dense all-pairs head_score")
+    for name, keys in {"dense": k, "strided": kr.StridedKeys(bshd_layers(k)), "paged": kr.PagedKeys(pools, table, S)}.items():
+        out = kr.all_pairs_similarity_in_place(q, keys, flags=flags, want_head_score=True)
+        torch.cuda.synchronize()
+        for n in ("pair_score", "pair_dist", "head_score"):
+            np.testing.assert_array_equal(out[n].cpu().numpy(), ref[n].cpu().numpy(), err_msg=f"{name} {n}")
+    del keep
+
+
 def test_in_place_calls_want_exactly_one_source(G):
     import ctypes
     import paper_2507_08045_amd as kr
