@@ -24,19 +24,35 @@ __global__ __launch_bounds__(kSelThreads) void select_pairs_kernel(
 // Averages over the heads (in order, as finalize_pairs_kernel takes them: the same bits) and the greedy
 // choice of every conversation in one workgroup: for small problems, where each further launch costs
 // more than the work in it.
-__global__ __launch_bounds__(kSelThreads) void pairs_select_kernel(PairsSelectArgs a)
+constexpr int kPsThreads = 1024;
+constexpr int kPsLoads = (kPairsSelectMaxHeads + kPsThreads - 1) / kPsThreads;   // head values per thread
+
+__global__ __launch_bounds__(kPsThreads) void pairs_select_kernel(PairsSelectArgs a)
 {
     extern __shared__ unsigned char sel_smem[];
     const int NP = a.L - 1, n_pairs_total = a.B * NP, n = n_pairs_total * a.Hq;
     float *vc = reinterpret_cast<float *>(sel_smem);   // [n] head cosines
     float *vd = vc + n;                                // [n] head distances
     float *pc = vd + n;                                // [n_pairs_total] pair scores
-    for (int i = threadIdx.x; i < n; i += kSelThreads) {
-        vc[i] = a.head_cos[i];
-        if (a.head_dist) vd[i] = a.head_dist[i];
+    {   // all loads of a thread are issued before the first is waited for: one memory latency, not one per value
+        float c[kPsLoads], dd[kPsLoads];
+#pragma unroll
+        for (int u = 0; u < kPsLoads; ++u) {
+            const int i = threadIdx.x + u * kPsThreads;
+            c[u] = i < n ? a.head_cos[i] : 0.f;
+            dd[u] = i < n && a.head_dist ? a.head_dist[i] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kPsLoads; ++u) {
+            const int i = threadIdx.x + u * kPsThreads;
+            if (i < n) {
+                vc[i] = c[u];
+                vd[i] = dd[u];
+            }
+        }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < n_pairs_total; i += kSelThreads) {
+    for (int i = threadIdx.x; i < n_pairs_total; i += kPsThreads) {
         float cs = 0.f, ds = 0.f;
 #pragma unroll 8
         for (int h = 0; h < a.Hq; ++h) {
@@ -62,7 +78,7 @@ hipError_t launch_pairs_select(const PairsSelectArgs &a, hipStream_t st)
 {
     const int n_pairs_total = a.B * (a.L - 1);
     const size_t smem = (size_t)(2 * n_pairs_total * a.Hq + n_pairs_total) * sizeof(float) + select_scratch_bytes(a.L);
-    hipLaunchKernelGGL(pairs_select_kernel, dim3(1), dim3(kSelThreads), smem, st, a);
+    hipLaunchKernelGGL(pairs_select_kernel, dim3(1), dim3(kPsThreads), smem, st, a);
     return hipGetLastError();
 }
 
