@@ -106,8 +106,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"],
-                    help="C5 draws 22.5 GiB of inputs on the host first (minutes); give it few --steps")
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "D1", "D2", "D3"],
+                    help="C5 draws 22.5 GiB of inputs on the host first (minutes); give it few --steps.  D1..D3 are "
+                         "decode-step shapes (one query token), not among the benchmark's configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--with-dist", action="store_true",

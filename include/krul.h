@@ -269,10 +269,10 @@ int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
 
 /*
  * Alg. 1's scoring and greedy choice (Sec. 4.2) in one call: krul_pair_similarity followed by
- * krul_select_pairs on its pair_score, with the same results bit for bit.  When the problem is small
- * (batch * (n_layers-1) * n_q_heads <= 4096 and batch <= 16) the averages over heads and the selection run
- * in one single-workgroup kernel, which saves a launch of a few microseconds; otherwise the same kernels
- * run as for the two calls.
+ * krul_select_pairs on its pair_score, with the same results bit for bit.  Unless a conversation has more
+ * than 16384 (pair, head) values, the averages over heads and the selection run in one kernel (a workgroup
+ * per conversation), which saves a launch of a few microseconds; otherwise the same kernels run as for the
+ * two calls.
  *
  *   eligible, n_select, out_pairs, out_count   as for krul_select_pairs (eligible is an input here: take it
  *                                              from an earlier krul_pair_similarity_ir, or pass NULL)

@@ -276,7 +276,7 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
         return KRUL_ELAUNCH;
     float *head_cos = head_score ? head_score : reinterpret_cast<float *>(ws + pl.head_cos_off);
     float *head_dist = accumulate ? pair_dist : reinterpret_cast<float *>(ws + pl.head_dist_off);
-    if (sel && pairs_select_fits(p.B, p.L, p.Hq)) {   // head scores, then pairs and selection in one small launch
+    if (sel && pairs_select_fits(p.L, p.Hq)) {   // head scores, then pairs and selection in one small launch
         e = launch_finalize(pl.lay, p.state, p.B, p.L, p.Hq, p.Hkv, p.Tq, head_cos, head_dist, nullptr,
                             pair_dist, false, st);
         if (e == hipSuccess) {

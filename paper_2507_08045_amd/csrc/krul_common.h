@@ -98,7 +98,7 @@ struct SimParams {
     StateLayout lay;
 };
 
-// Head averages and the greedy choice in one single-workgroup kernel (krul_pair_similarity_select).
+// Head averages and the greedy choice in one kernel, a workgroup per conversation (krul_pair_similarity_select).
 struct PairsSelectArgs {
     const float *head_cos, *head_dist;   // [B][L-1][Hq]; head_dist may be null
     float *pair_cos, *pair_dist;         // [B][L-1]; pair_dist may be null
@@ -106,8 +106,7 @@ struct PairsSelectArgs {
     int B, L, Hq, n_select;
     int32_t *out_pairs, *out_count;
 };
-constexpr int kPairsSelectMaxHeads = 4096;   // B * (L-1) * Hq that one workgroup averages and ranks
-constexpr int kPairsSelectMaxBatch = 16;
+constexpr int kPairsSelectMaxHeads = 16384;   // (L-1) * Hq head values that one workgroup averages and ranks
 
 // Host: shape checks common to all entry points.  Returns a krul_status_t.
 int check_shape(const krul_shape_t *s);
@@ -149,9 +148,9 @@ hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
 hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, int L, int Hq, int Hkv,
                            int Tq, float *head_cos, float *head_dist, float *pair_cos,
                            float *pair_dist, bool accumulate, hipStream_t st);
-// Pair scores from head scores and the selection of every conversation, one workgroup
-// (pairs_select_fits says whether the problem is small enough for that).
-bool pairs_select_fits(int B, int L, int Hq);
+// Pair scores from head scores and the selection, one workgroup per conversation
+// (pairs_select_fits says whether a conversation's head values fit one).
+bool pairs_select_fits(int L, int Hq);
 hipError_t launch_pairs_select(const PairsSelectArgs &a, hipStream_t st);
 // head sums -> head and pair scores (head_dist_sum, head_score, pair_dist may be null)
 hipError_t launch_scores_from_sums(const float *head_sum, const float *head_dist_sum, int n_pairs_total,

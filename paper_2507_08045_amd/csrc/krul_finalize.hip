@@ -50,24 +50,31 @@ __device__ inline void merge_into(RowAcc &r, float ma, float za, float na, float
 // G lanes of a wave (G a power of two, lanes g*(64/G) + r for g < G) share one query row:
 // each merges the partials p = g, g+G, ... and a butterfly over g joins them.  Lanes with
 // the same g read consecutive rows, i.e. consecutive records.
+//
+// PER_WAVE (few rows: all of a head's rows fit the lanes of one wave, G * Tq <= 64): every wave takes a
+// (conversation, pair, query head) of its own and sums the rows by shuffles -- a decode step has one row
+// per head, and a workgroup per head would be 252 idle threads and four times the workgroups.
+template <bool PER_WAVE>
 __global__ __launch_bounds__(kThreads) void finalize_heads_kernel(
     StateLayout lay, const float4 *__restrict__ state, int L, int Hq, int Hkv, int Tq, int G,
-    int want_dist, int accumulate, float *__restrict__ head_cos, float *__restrict__ head_dist)
+    int want_dist, int accumulate, int n_items, float *__restrict__ head_cos, float *__restrict__ head_dist)
 {
     __shared__ float red[kThreads / 64];
     const int NP = L - 1;
-    const int h = blockIdx.x % Hq;
-    const int l = (blockIdx.x / Hq) % NP;
-    const int b = blockIdx.x / (Hq * NP);
+    const int item = PER_WAVE ? blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6) : blockIdx.x;
+    if (PER_WAVE && item >= n_items) return;   // (a whole wave: no barrier follows in this form)
+    const int h = item % Hq;
+    const int l = (item / Hq) % NP;
+    const int b = item / (Hq * NP);
     const int g_heads = Hq / Hkv;
     const int u = b * Hkv + h / g_heads;
     const int P = lay.partials;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = PER_WAVE ? 0 : threadIdx.x >> 6;
     const int RW = 64 / G;                       // rows per wave
     const int rr = lane % RW, g = lane / RW;
 
     float cos_acc = 0.f, dist_acc = 0.f;
-    for (int t0 = 0; t0 < Tq; t0 += (kThreads / 64) * RW) {
+    for (int t0 = 0; t0 < Tq; t0 += (PER_WAVE ? 1 : kThreads / 64) * RW) {
         const int t = t0 + wave * RW + rr;
         RowAcc acc = {kMInit, 0.f, 0.f, kMInit, 0.f, 0.f, 0.f};
         if (t < Tq) {
@@ -94,15 +101,24 @@ __global__ __launch_bounds__(kThreads) void finalize_heads_kernel(
             }
         }
     }
-    const float cs = block_sum(cos_acc, red);
-    const float ds = block_sum(dist_acc, red);
-    if (threadIdx.x == 0) {
+    float cs = cos_acc, ds = dist_acc;
+    if constexpr (PER_WAVE) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            cs += __shfl_xor(cs, o, 64);
+            ds += __shfl_xor(ds, o, 64);
+        }
+    } else {
+        cs = block_sum(cos_acc, red);
+        ds = block_sum(dist_acc, red);
+    }
+    if ((PER_WAVE ? lane : (int)threadIdx.x) == 0) {
         if (accumulate) {   // token-wise running sums over several calls (Sec. 5, Sec. 7 "adds up")
-            head_cos[blockIdx.x] += cs;
-            if (want_dist) head_dist[blockIdx.x] += ds;
+            head_cos[item] += cs;
+            if (want_dist) head_dist[item] += ds;
         } else {
-            head_cos[blockIdx.x] = cs / (float)Tq;
-            head_dist[blockIdx.x] = ds / (float)Tq;
+            head_cos[item] = cs / (float)Tq;
+            head_dist[item] = ds / (float)Tq;
         }
     }
 }
@@ -213,8 +229,18 @@ hipError_t launch_finalize(const StateLayout &lay, const float4 *state, int B, i
     // lanes per row: enough to keep a workgroup's 256 threads busy, at most one per partial
     int G = 1;
     while (G < 64 && G * Tq < kThreads && G < lay.partials) G <<= 1;
-    hipLaunchKernelGGL(finalize_heads_kernel, dim3(n_pairs_total * Hq), dim3(kThreads), 0, st, lay,
-                       state, L, Hq, Hkv, Tq, G, pair_dist != nullptr, accumulate ? 1 : 0, head_cos, head_dist);
+    const int n_items = n_pairs_total * Hq;
+    if (Tq <= 8) {   // few rows: a wave per head, G lanes per row with G * Tq <= 64
+        G = 1;
+        while (G * 2 * Tq <= 64 && G < lay.partials) G <<= 1;
+        hipLaunchKernelGGL(finalize_heads_kernel<true>, dim3((n_items + kThreads / 64 - 1) / (kThreads / 64)),
+                           dim3(kThreads), 0, st, lay, state, L, Hq, Hkv, Tq, G, pair_dist != nullptr,
+                           accumulate ? 1 : 0, n_items, head_cos, head_dist);
+    } else {
+        hipLaunchKernelGGL(finalize_heads_kernel<false>, dim3(n_items), dim3(kThreads), 0, st, lay,
+                           state, L, Hq, Hkv, Tq, G, pair_dist != nullptr, accumulate ? 1 : 0, n_items, head_cos,
+                           head_dist);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || accumulate || !pair_cos) return e;   // (no pair scores asked for: the caller forms them)
     hipLaunchKernelGGL(finalize_pairs_kernel, dim3((n_pairs_total + 127) / 128), dim3(128), 0, st,

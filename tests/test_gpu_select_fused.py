@@ -21,13 +21,13 @@ def G():
 # (name, B, L, Hq, Hkv, d, S, Tq, dtype, n_select, with_eligible)
 CASES = [
     ("sel-wide", 1, 12, 8, 2, 128, 1500, 40, "bf16", 4, False),        # several key splits, one conversation
-    ("sel-batch", 3, 9, 4, 2, 64, 700, 6, "bf16", 3, True),            # three conversations in the last workgroup
+    ("sel-batch", 3, 9, 4, 2, 64, 700, 6, "bf16", 3, True),            # three conversations, a workgroup each
     ("sel-f32", 2, 6, 4, 2, 64, 300, 5, "f32", 2, True),               # portable similarity kernel
     ("sel-two-layers", 1, 2, 2, 1, 64, 40, 1, "bf16", 1, False),
     ("sel-none", 2, 5, 4, 4, 128, 90, 2, "f16", 0, False),             # n_select = 0
-    ("sel-many-heads", 2, 40, 64, 8, 64, 200, 1, "bf16", 10, True),    # 2*39*64 = 4992 head values: separate kernels
-    ("sel-many-conversations", 20, 4, 2, 2, 64, 130, 2, "bf16", 2, True),   # batch > 16: separate kernels
-    ("sel-at-the-limit", 2, 33, 64, 8, 64, 150, 1, "bf16", 16, False),  # 2*32*64 = 4096: the largest fused case
+    ("sel-many-heads", 2, 130, 128, 8, 64, 100, 1, "bf16", 10, True),    # 129*128 = 16512 head values a conversation: separate kernels
+    ("sel-many-conversations", 20, 4, 2, 2, 64, 130, 2, "bf16", 2, True),
+    ("sel-at-the-limit", 2, 129, 128, 8, 64, 100, 1, "bf16", 16, False),  # 128*128 = 16384: the largest conversation one workgroup takes
 ]
 
 

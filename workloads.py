@@ -35,8 +35,13 @@ CONFIGS = {
     "C3": (1, 32, 32, 8, 128, 32768, 16, "bf16", 8),
     "C4": (1, 32, 32, 8, 128, 8192, 2048, "bf16", 8),
     "C5": (8, 80, 64, 8, 128, 16384, 256, "bf16", 20),
+    # decode steps (one query token per conversation; the token-wise scoring of Sec. 5) -- not among the
+    # benchmark's five configurations, kept here so that their measurements can be repeated
+    "D1": (8, 32, 32, 8, 128, 4096, 1, "bf16", 8),      # eight conversations, 4096 tokens each
+    "D2": (1, 32, 32, 8, 128, 131072, 1, "bf16", 8),    # one long conversation
+    "D3": (1, 32, 32, 8, 128, 4096, 1, "bf16", 8),      # one short conversation: too small to fill the chip
 }
-_CFG_ID = {"C1": 1, "C2": 2, "C3": 3, "C4": 4, "C5": 5}
+_CFG_ID = {"C1": 1, "C2": 2, "C3": 3, "C4": 4, "C5": 5, "D1": 6, "D2": 7, "D3": 8}
 
 
 @dataclass
@@ -118,7 +123,8 @@ def make(name: str = "custom", *, B, L, Hq, Hkv, d, S, Tq, dtype="bf16", n_selec
 
 
 def config(name: str, *, batch=None, seed=None, progress=None) -> Workload:
-    """One of the five benchmark configurations C1..C5 (full size unless batch is cut)."""
+    """One of the benchmark configurations C1..C5, or of the decode-step shapes D1..D3 (full size unless batch
+    is cut)."""
     B, L, Hq, Hkv, d, S, Tq, dtype, n_select = CONFIGS[name]
     if batch is not None:
         B = batch
@@ -131,7 +137,7 @@ def config(name: str, *, batch=None, seed=None, progress=None) -> Workload:
         rho = rr.uniform(0.5, 0.95, size=(B, L - 1, Hkv))   # varies per pair and per kv head
     else:
         rho = rr.uniform(0.5, 0.95, size=(B, L - 1, 1))     # one rho per pair
-    if name == "C3":
+    if name in ("C3", "D2"):
         kw = dict(sink_frac=0.02, sink_gain=4.0)
     return make(name, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, dtype=dtype, n_select=n_select,
                 rho_k=rho, seed=seed, progress=progress, **kw)
