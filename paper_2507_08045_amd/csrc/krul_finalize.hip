@@ -145,23 +145,27 @@ __global__ void finalize_pairs_kernel(int n_pairs_total, int Hq, float scale, co
 // Initial-Recent layer test (Sec. 4.2; Alg. 1 first loop): per (conversation, layer, head) the
 // mean over query rows of Zir / Z -- the attention mass on T_initial and T_recent -- from the
 // partial records of each row, merged onto a common exponent like the similarity sums.
+// (PER_WAVE: as for finalize_heads_kernel)
+template <bool PER_WAVE>
 __global__ __launch_bounds__(kThreads) void ir_heads_kernel(
     StateLayout lay, const float4 *__restrict__ state, const float *__restrict__ state_ir, int L, int Hq,
-    int Hkv, int Tq, int G, float *__restrict__ head_ir)
+    int Hkv, int Tq, int G, int n_items, float *__restrict__ head_ir)
 {
     __shared__ float red[kThreads / 64];
-    const int h = blockIdx.x % Hq;
-    const int l = (blockIdx.x / Hq) % L;
-    const int b = blockIdx.x / (Hq * L);
+    const int item = PER_WAVE ? blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6) : blockIdx.x;
+    if (PER_WAVE && item >= n_items) return;   // (a whole wave: no barrier follows in this form)
+    const int h = item % Hq;
+    const int l = (item / Hq) % L;
+    const int b = item / (Hq * L);
     const int g_heads = Hq / Hkv;
     const int u = b * Hkv + h / g_heads;
     const int P = lay.partials;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = PER_WAVE ? 0 : threadIdx.x >> 6;
     const int RW = 64 / G;                       // rows per wave, G lanes per row
     const int rr = lane % RW, g = lane / RW;
 
     float mass_acc = 0.f;
-    for (int t0 = 0; t0 < Tq; t0 += (kThreads / 64) * RW) {
+    for (int t0 = 0; t0 < Tq; t0 += (PER_WAVE ? 1 : kThreads / 64) * RW) {
         const int t = t0 + wave * RW + rr;
         float M = kMInit, Z = 0.f, I = 0.f;
         if (t < Tq) {
@@ -187,8 +191,14 @@ __global__ __launch_bounds__(kThreads) void ir_heads_kernel(
         }
         if (t < Tq && g == 0) mass_acc += I / Z;
     }
-    const float ms = block_sum(mass_acc, red);
-    if (threadIdx.x == 0) head_ir[blockIdx.x] = ms / (float)Tq;
+    float ms = mass_acc;
+    if constexpr (PER_WAVE) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ms += __shfl_xor(ms, o, 64);
+    } else {
+        ms = block_sum(mass_acc, red);
+    }
+    if ((PER_WAVE ? lane : (int)threadIdx.x) == 0) head_ir[item] = ms / (float)Tq;
 }
 
 // one thread per (conversation, layer): the average over heads, and the test against gamma
@@ -212,8 +222,16 @@ hipError_t launch_finalize_ir(const StateLayout &lay, const float4 *state, const
 {
     int G = 1;
     while (G < 64 && G * Tq < kThreads && G < lay.partials) G <<= 1;
-    hipLaunchKernelGGL(ir_heads_kernel, dim3(B * L * Hq), dim3(kThreads), 0, st, lay, state, state_ir, L, Hq,
-                       Hkv, Tq, G, head_ir);
+    const int n_items = B * L * Hq;
+    if (Tq <= 8) {   // few rows: a wave per head, G lanes per row with G * Tq <= 64
+        G = 1;
+        while (G * 2 * Tq <= 64 && G < lay.partials) G <<= 1;
+        hipLaunchKernelGGL(ir_heads_kernel<true>, dim3((n_items + kThreads / 64 - 1) / (kThreads / 64)), dim3(kThreads),
+                           0, st, lay, state, state_ir, L, Hq, Hkv, Tq, G, n_items, head_ir);
+    } else {
+        hipLaunchKernelGGL(ir_heads_kernel<false>, dim3(n_items), dim3(kThreads), 0, st, lay, state, state_ir, L, Hq,
+                           Hkv, Tq, G, n_items, head_ir);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(ir_layers_kernel, dim3((B * L + 127) / 128), dim3(128), 0, st, B * L, Hq, gamma, head_ir,
