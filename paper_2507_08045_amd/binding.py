@@ -200,6 +200,62 @@ def pair_similarity(q: torch.Tensor, k: torch.Tensor, *, scale: float = 0.0, fla
     return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace}
 
 
+class StridedKeys:
+    """Keys in one GPU tensor per layer, each indexed [B, Hkv, S, d] (see pair_similarity_strided)."""
+
+    def __init__(self, k_layers):
+        self.k_layers = list(k_layers)
+        self.table = None
+
+
+class PagedKeys:
+    """Keys in one pool of pages per layer and a block table (see pair_similarity_paged); n_hist keys per
+    conversation."""
+
+    def __init__(self, pools, block_table: torch.Tensor, n_hist: int):
+        self.pools, self.block_table, self.n_hist = list(pools), block_table, int(n_hist)
+        self.table = None
+
+
+def _keys(q: torch.Tensor, keys, scale: float, flags: int):
+    """(shape, KrulKeys, objects to keep alive) for dense keys (a tensor), StridedKeys or PagedKeys."""
+    if not q.is_cuda or q.dim() != 5 or not q.is_contiguous() or q.dtype not in _DTYPES:
+        raise ValueError("q must be a contiguous GPU tensor [B,L,Hq,Tq,d] of dtype float32, bfloat16 or float16")
+    B, L, Hq, Tq, d = q.shape
+    if isinstance(keys, torch.Tensor):
+        if not keys.is_cuda or not keys.is_contiguous():
+            raise ValueError("k must be a contiguous GPU tensor")
+        return make_shape(q, keys, scale, flags), KrulKeys(keys.data_ptr(), None, None), (keys,)
+    layers = keys.k_layers if isinstance(keys, StridedKeys) else keys.pools
+    t0 = layers[0]
+    if len(layers) != L or any(not t.is_cuda or t.dim() != 4 or t.shape != t0.shape or t.stride() != t0.stride()
+                               or t.dtype != q.dtype for t in layers) or t0.stride(3) != 1 or t0.shape[3] != d:
+        raise ValueError("one 4-d GPU tensor per layer, all of one shape, one set of strides, q's dtype and head_dim")
+    if keys.table is None:
+        keys.table = torch.tensor([t.data_ptr() for t in layers], dtype=torch.int64).to(q.device)
+    if isinstance(keys, StridedKeys):
+        if t0.shape[0] != B:
+            raise ValueError("q and k disagree on the batch")
+        shp = KrulShape(B, L, Hq, t0.shape[1], d, t0.shape[2], Tq, _DTYPES[q.dtype], float(scale), int(flags))
+        lay = KrulKLayout(keys.table.data_ptr(), t0.stride(0) if B > 1 else 0, t0.stride(1), t0.stride(2))
+        return shp, KrulKeys(None, ctypes.pointer(lay), None), (lay, keys)
+    bt = keys.block_table
+    if not bt.is_cuda or bt.dtype != torch.int32 or bt.dim() != 2 or not bt.is_contiguous() or bt.shape[0] != B:
+        raise ValueError("block_table must be a contiguous int32 GPU tensor [B, max_blocks]")
+    shp = KrulShape(B, L, Hq, t0.shape[2], d, keys.n_hist, Tq, _DTYPES[q.dtype], float(scale), int(flags))
+    pages = KrulKPages(keys.table.data_ptr(), bt.data_ptr(), t0.shape[1], bt.shape[1], t0.stride(0), t0.stride(2),
+                       t0.stride(1))
+    return shp, KrulKeys(None, None, ctypes.pointer(pages)), (pages, keys)
+
+
+def _pair_outputs(shp, q, want_head_score, want_pair_dist):
+    B, L, Hq = shp.batch, shp.n_layers, shp.n_q_heads
+    ps = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
+    hs = torch.empty((B, L - 1, Hq), dtype=torch.float32, device=q.device) if want_head_score else None
+    pd = torch.empty((B, L - 1), dtype=torch.float32, device=q.device) if want_pair_dist else None
+    return ps, hs, pd
+
+
 def pair_similarity_strided(q: torch.Tensor, k_layers, *, scale: float = 0.0, flags: int = 0,
                             want_head_score: bool = True, want_pair_dist: bool = True,
                             workspace: torch.Tensor | None = None, k_table: torch.Tensor | None = None) -> dict:
@@ -208,38 +264,21 @@ def pair_similarity_strided(q: torch.Tensor, k_layers, *, scale: float = 0.0, fl
     contiguous head_dim, e.g. cache[l].permute(0, 2, 1, 3) of a [B, S, Hkv, d] cache.  k_table: the
     device array of the layers' addresses from an earlier call with the same tensors (returned as
     "k_table"), to skip its upload."""
-    if not q.is_cuda or not all(t.is_cuda for t in k_layers):
-        raise ValueError("q and k must be GPU tensors (this library has no CPU path)")
-    if not q.is_contiguous():
-        raise ValueError("q must be contiguous")
-    k0 = k_layers[0]
-    if q.dim() != 5 or any(t.dim() != 4 or t.shape != k0.shape or t.stride() != k0.stride() or t.dtype != q.dtype
-                           for t in k_layers):
-        raise ValueError("q must be [B,L,Hq,Tq,d] and every k_layers[l] a [B,Hkv,S,d] view of one shape, "
-                         "one set of strides and q's dtype")
-    if k0.stride(3) != 1 or q.dtype not in _DTYPES:
-        raise ValueError("head_dim must be contiguous; dtype float32, bfloat16 or float16")
-    B, L, Hq, Tq, d = q.shape
-    if len(k_layers) != L or k0.shape[0] != B or k0.shape[3] != d:
-        raise ValueError("q and k disagree on batch, layers or head_dim")
-    shp = KrulShape(B, L, Hq, k0.shape[1], d, k0.shape[2], Tq, _DTYPES[q.dtype],
-                    float(scale), int(flags))
-    if k_table is None:
-        k_table = torch.tensor([t.data_ptr() for t in k_layers], dtype=torch.int64).to(q.device)
-    lay = KrulKLayout(k_table.data_ptr(), k0.stride(0) if B > 1 else 0, k0.stride(1), k0.stride(2))
+    keys = StridedKeys(k_layers)
+    keys.table = k_table
+    shp, ks, keep = _keys(q, keys, scale, flags)
     need = workspace_bytes(shp)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
-    ps = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
-    hs = torch.empty((B, L - 1, Hq), dtype=torch.float32, device=q.device) if want_head_score else None
-    pd = torch.empty((B, L - 1), dtype=torch.float32, device=q.device) if want_pair_dist else None
-    rc = lib().krul_pair_similarity_strided(ctypes.byref(shp), _dev_ptr(q), ctypes.byref(lay), _dev_ptr(ps),
+    ps, hs, pd = _pair_outputs(shp, q, want_head_score, want_pair_dist)
+    rc = lib().krul_pair_similarity_strided(ctypes.byref(shp), _dev_ptr(q), ks.strided, _dev_ptr(ps),
                                             _dev_ptr(hs), _dev_ptr(pd), _dev_ptr(workspace),
                                             workspace.numel() if workspace is not None else 0,
                                             ctypes.c_void_p(_stream_ptr()))
+    del keep
     if rc != KRUL_OK:
         raise KrulError(rc)
-    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace, "k_table": k_table}
+    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace, "k_table": keys.table}
 
 
 def pair_similarity_paged(q: torch.Tensor, pools, block_table: torch.Tensor, n_hist: int, *, scale: float = 0.0,
@@ -248,38 +287,21 @@ def pair_similarity_paged(q: torch.Tensor, pools, block_table: torch.Tensor, n_h
     """krul_pair_similarity_paged on the current stream.  pools: one GPU tensor per layer indexed
     [page, key in page, kv head, d] with any strides over the first three axes (the same for every layer) and
     contiguous head_dim; block_table: int32 GPU tensor [B, max_blocks]; n_hist: keys per conversation."""
-    if not q.is_cuda or not all(t.is_cuda for t in pools) or not block_table.is_cuda:
-        raise ValueError("q, the pools and the block table must be GPU tensors (this library has no CPU path)")
-    p0 = pools[0]
-    if q.dim() != 5 or not q.is_contiguous() or any(t.dim() != 4 or t.stride() != p0.stride() or t.dtype != q.dtype
-                                                     for t in pools):
-        raise ValueError("q must be contiguous [B,L,Hq,Tq,d]; every pool a [pages, block, Hkv, d] tensor with one "
-                         "set of strides and q's dtype")
-    if p0.stride(3) != 1 or q.dtype not in _DTYPES:
-        raise ValueError("head_dim must be contiguous; dtype float32, bfloat16 or float16")
-    if block_table.dtype != torch.int32 or block_table.dim() != 2 or not block_table.is_contiguous():
-        raise ValueError("block_table must be a contiguous int32 tensor [B, max_blocks]")
-    B, L, Hq, Tq, d = q.shape
-    if len(pools) != L or block_table.shape[0] != B or p0.shape[3] != d:
-        raise ValueError("q, the pools and the block table disagree on batch, layers or head_dim")
-    shp = KrulShape(B, L, Hq, p0.shape[2], d, int(n_hist), Tq, _DTYPES[q.dtype], float(scale), int(flags))
-    if k_table is None:
-        k_table = torch.tensor([t.data_ptr() for t in pools], dtype=torch.int64).to(q.device)
-    pages = KrulKPages(k_table.data_ptr(), block_table.data_ptr(), p0.shape[1], block_table.shape[1],
-                       p0.stride(0), p0.stride(2), p0.stride(1))
+    keys = PagedKeys(pools, block_table, n_hist)
+    keys.table = k_table
+    shp, ks, keep = _keys(q, keys, scale, flags)
     need = workspace_bytes(shp)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
-    ps = torch.empty((B, L - 1), dtype=torch.float32, device=q.device)
-    hs = torch.empty((B, L - 1, Hq), dtype=torch.float32, device=q.device) if want_head_score else None
-    pd = torch.empty((B, L - 1), dtype=torch.float32, device=q.device) if want_pair_dist else None
-    rc = lib().krul_pair_similarity_paged(ctypes.byref(shp), _dev_ptr(q), ctypes.byref(pages), _dev_ptr(ps),
+    ps, hs, pd = _pair_outputs(shp, q, want_head_score, want_pair_dist)
+    rc = lib().krul_pair_similarity_paged(ctypes.byref(shp), _dev_ptr(q), ks.paged, _dev_ptr(ps),
                                           _dev_ptr(hs), _dev_ptr(pd), _dev_ptr(workspace),
                                           workspace.numel() if workspace is not None else 0,
                                           ctypes.c_void_p(_stream_ptr()))
+    del keep
     if rc != KRUL_OK:
         raise KrulError(rc)
-    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace, "k_table": k_table}
+    return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace, "k_table": keys.table}
 
 
 def pair_similarity_ir(q: torch.Tensor, k: torch.Tensor, gamma: float, *, scale: float = 0.0, flags: int = 0,
@@ -336,54 +358,6 @@ def pair_similarity_accumulate(q: torch.Tensor, k: torch.Tensor, head_sum: torch
     if rc != KRUL_OK:
         raise KrulError(rc)
     return workspace
-
-
-class StridedKeys:
-    """Keys in one GPU tensor per layer, each indexed [B, Hkv, S, d] (see pair_similarity_strided)."""
-
-    def __init__(self, k_layers):
-        self.k_layers = list(k_layers)
-        self.table = None
-
-
-class PagedKeys:
-    """Keys in one pool of pages per layer and a block table (see pair_similarity_paged); n_hist keys per
-    conversation."""
-
-    def __init__(self, pools, block_table: torch.Tensor, n_hist: int):
-        self.pools, self.block_table, self.n_hist = list(pools), block_table, int(n_hist)
-        self.table = None
-
-
-def _keys(q: torch.Tensor, keys, scale: float, flags: int):
-    """(shape, KrulKeys, objects to keep alive) for dense keys (a tensor), StridedKeys or PagedKeys."""
-    if not q.is_cuda or q.dim() != 5 or not q.is_contiguous() or q.dtype not in _DTYPES:
-        raise ValueError("q must be a contiguous GPU tensor [B,L,Hq,Tq,d] of dtype float32, bfloat16 or float16")
-    B, L, Hq, Tq, d = q.shape
-    if isinstance(keys, torch.Tensor):
-        if not keys.is_cuda or not keys.is_contiguous():
-            raise ValueError("k must be a contiguous GPU tensor")
-        return make_shape(q, keys, scale, flags), KrulKeys(keys.data_ptr(), None, None), (keys,)
-    layers = keys.k_layers if isinstance(keys, StridedKeys) else keys.pools
-    t0 = layers[0]
-    if len(layers) != L or any(not t.is_cuda or t.dim() != 4 or t.shape != t0.shape or t.stride() != t0.stride()
-                               or t.dtype != q.dtype for t in layers) or t0.stride(3) != 1 or t0.shape[3] != d:
-        raise ValueError("one 4-d GPU tensor per layer, all of one shape, one set of strides, q's dtype and head_dim")
-    if keys.table is None:
-        keys.table = torch.tensor([t.data_ptr() for t in layers], dtype=torch.int64).to(q.device)
-    if isinstance(keys, StridedKeys):
-        if t0.shape[0] != B:
-            raise ValueError("q and k disagree on the batch")
-        shp = KrulShape(B, L, Hq, t0.shape[1], d, t0.shape[2], Tq, _DTYPES[q.dtype], float(scale), int(flags))
-        lay = KrulKLayout(keys.table.data_ptr(), t0.stride(0) if B > 1 else 0, t0.stride(1), t0.stride(2))
-        return shp, KrulKeys(None, ctypes.pointer(lay), None), (lay, keys)
-    bt = keys.block_table
-    if not bt.is_cuda or bt.dtype != torch.int32 or bt.dim() != 2 or not bt.is_contiguous() or bt.shape[0] != B:
-        raise ValueError("block_table must be a contiguous int32 GPU tensor [B, max_blocks]")
-    shp = KrulShape(B, L, Hq, t0.shape[2], d, keys.n_hist, Tq, _DTYPES[q.dtype], float(scale), int(flags))
-    pages = KrulKPages(keys.table.data_ptr(), bt.data_ptr(), t0.shape[1], bt.shape[1], t0.stride(0), t0.stride(2),
-                       t0.stride(1))
-    return shp, KrulKeys(None, None, ctypes.pointer(pages)), (pages, keys)
 
 
 def pair_similarity_accumulate_in_place(q: torch.Tensor, keys, head_sum: torch.Tensor,
