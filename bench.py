@@ -30,6 +30,17 @@ def algorithmic_flops(w) -> int:
     return 2 * w.d * w.B * w.L * w.Hq * w.Tq * w.S
 
 
+def algorithmic_valu_ops(w, with_dist=False) -> int:
+    """Vector-unit issue slots per logit, per lane: scale-and-shift fma, exp2 (two slots), the fma into the sum of
+    squares and the fma into the cross term (+ one add into the plain sum when the distance is asked for)."""
+    return (6 if with_dist else 5) * w.B * w.L * w.Hq * w.Tq * w.S
+
+
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: lane operations per second of the vector units, one operation per
+# lane and issue slot (the packed-fp32 forms, which would double it, are compiled out)
+VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
 def cpu_baseline(w, seconds_target=15.0):
     """The fp64 oracle, as it stands, on a bounded sample of (b, pair, head) units."""
     import numpy as np
@@ -226,6 +237,11 @@ def main():
                      "kernel_us": kern_s * 1e6, "kernel_us_samples": len(kern_ms), "algorithmic_bytes": bytes_alg},
         "roofline_mfma": {"bound": "mfma", "achieved": mfma_tflops, "peak": 2500.0, "unit": "TFLOP/s",
                           "frac": mfma_tflops / 2500.0, "algorithmic_flops": flops_alg},
+        # the matrix and the vector instructions of a wave share its issue slots and overlap only partly, so
+        # the kernel's compute floor is close to the SUM of these two fractions, not their maximum
+        "roofline_alu": {"bound": "alu", "achieved": algorithmic_valu_ops(w, args.with_dist) / kern_s / 1e12,
+                         "peak": VALU_PEAK_TOPS, "unit": "T lane-op/s",
+                         "frac": algorithmic_valu_ops(w, args.with_dist) / kern_s / 1e12 / VALU_PEAK_TOPS},
         "selected_pairs": pairs.cpu().tolist()[0],
     }
     if not args.no_cpu_baseline:
