@@ -706,10 +706,82 @@ __global__ __launch_bounds__(kSelThreads) void select_all_kernel(
     const float *sc = score + (size_t)b * L * L;
     const bool in_lds = L <= kSelLdsLayers;
     for (int l = tid; l < L; l += kSelThreads) used[l] = eligible ? (eligible[(size_t)b * L + l] ? 0 : 1) : 0;
-    if (in_lds)
-        for (int e = tid; e < L * L; e += kSelThreads) keys[e] = closer_is_smaller ? sc[e] : -sc[e];
+    if (in_lds) {   // (four loads in flight per thread: one memory latency per four entries)
+        for (int e0 = 0; e0 < L * L; e0 += 4 * kSelThreads) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * kSelThreads + tid;
+                v[u] = e < L * L ? sc[e] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * kSelThreads + tid;
+                if (e < L * L) keys[e] = closer_is_smaller ? v[u] : -v[u];
+            }
+        }
+    }
     __syncthreads();
     int cnt = 0;
+    if (L <= 128 && in_lds) {
+        // Ordering keys in LDS (at most 96 layers): the layers in use are two 64-bit masks that every thread keeps for itself, and
+        // every thread works out the round's winner from the waves' candidates -- one barrier a round
+        // (the waves' candidates alternate between two sets of slots), no thread waits for thread 0.
+        const int ln = tid & 63;
+        unsigned long long used_lo = __ballot(ln < L && used[ln < L ? ln : 0]);
+        unsigned long long used_hi = __ballot(ln + 64 < L && used[ln + 64 < L ? ln + 64 : 0]);
+        auto is_used = [&](int l) { return ((l < 64 ? used_lo : used_hi) >> (l & 63)) & 1ull; };
+        float *bk2 = keys + L * L;                                  // [2][waves]
+        int *br2 = reinterpret_cast<int *>(bk2 + 2 * (kSelThreads / 64));
+        for (; cnt < n_select; ++cnt) {
+            float best = INFINITY;
+            int rank = INT32_MAX;   // j * L + i of the best candidate
+            for (int e = tid; e < L * L; e += kSelThreads) {
+                const int i = e / L, j = e % L;
+                if (i <= j || is_used(i) || is_used(j)) continue;
+                const float key = keys[e];
+                const int rk = j * L + i;
+                if (rank == INT32_MAX || key < best || (key == best && rk < rank)) {
+                    best = key;
+                    rank = rk;
+                }
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ob = __shfl_xor(best, o, 64);
+                const int orank = __shfl_xor(rank, o, 64);
+                if (orank != INT32_MAX && (rank == INT32_MAX || ob < best || (ob == best && orank < rank))) {
+                    best = ob;
+                    rank = orank;
+                }
+            }
+            const int set = (cnt & 1) * (kSelThreads / 64);
+            if ((tid & 63) == 0) {
+                bk2[set + (tid >> 6)] = best;
+                br2[set + (tid >> 6)] = rank;
+            }
+            __syncthreads();
+            float kb = bk2[set];
+            int rk = br2[set];
+#pragma unroll
+            for (int wv = 1; wv < kSelThreads / 64; ++wv) {
+                const float ob = bk2[set + wv];
+                const int orank = br2[set + wv];
+                if (orank != INT32_MAX && (rk == INT32_MAX || ob < kb || (ob == kb && orank < rk))) {
+                    kb = ob;
+                    rk = orank;
+                }
+            }
+            if (rk == INT32_MAX) break;   // no free candidate is left
+            const int j = rk / L, i = rk % L;
+            (i < 64 ? used_lo : used_hi) |= 1ull << (i & 63);
+            (j < 64 ? used_lo : used_hi) |= 1ull << (j & 63);
+            if (tid == 0) {
+                out_pairs[((size_t)b * n_select + cnt) * 2] = j;
+                out_pairs[((size_t)b * n_select + cnt) * 2 + 1] = i;
+            }
+        }
+    } else
     for (; cnt < n_select; ++cnt) {
         float best = INFINITY;
         int rank = INT32_MAX;   // j * L + i of the best candidate
@@ -985,7 +1057,10 @@ hipError_t launch_select_all(const float *score, int closer_is_smaller, const ui
                              int n_layers, int n_select, int32_t *out_pairs, int32_t *out_count, hipStream_t st)
 {
     const size_t smem = ((n_layers + 15) & ~15) + (kSelThreads / 64) * (sizeof(float) + sizeof(int));
-    const size_t smem_keys = n_layers <= kSelLdsLayers ? (size_t)n_layers * n_layers * sizeof(float) : 0;
+    // (+ two sets of per-wave candidates for the one-barrier rounds)
+    const size_t smem_keys = n_layers <= kSelLdsLayers
+                                 ? (size_t)n_layers * n_layers * sizeof(float) + 2 * (kSelThreads / 64) * (sizeof(float) + sizeof(int))
+                                 : 0;
     hipLaunchKernelGGL(select_all_kernel, dim3(batch), dim3(kSelThreads), smem + smem_keys, st, score, closer_is_smaller,
                        eligible, n_layers, n_select, out_pairs, out_count);
     return hipGetLastError();
