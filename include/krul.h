@@ -61,8 +61,9 @@ typedef struct {
     int32_t n_q_heads;    /* Hq  query heads                                       */
     int32_t n_kv_heads;   /* Hkv key heads, divides Hq; query head h reads kv head
                                  h / (Hq/Hkv)                                      */
-    int32_t head_dim;     /* d   64 or 128 for the matrix-core kernels (bf16, f16);
-                                 any multiple of 8 up to 256 for the portable one  */
+    int32_t head_dim;     /* d   a multiple of 8: up to 128 for the matrix-core
+                                 kernels (bf16, f16; sizes other than 64 and 128 ride
+                                 zero-padded), up to 256 for the portable one       */
     int32_t n_hist;       /* S   history keys per layer (every query row sees all) */
     int32_t n_query;      /* Tq  query rows (tokens) per head                      */
     int32_t dtype;        /* krul_dtype_t of q and k                               */
@@ -138,8 +139,8 @@ int krul_pair_similarity_ir(const krul_shape_t *shape, const void *q, const void
  *               elements between conversations, kv heads and keys inside a layer: key (b, h, j) starts at
  *               k_layers[l] + b*k_stride_b + h*k_stride_h + j*k_stride_s; its head_dim elements are
  *               contiguous.  All > 0 and multiples of 8 elements (k_stride_b is ignored for batch 1),
- *               k_stride_s >= head_dim (else KRUL_EINVAL); for bf16 / f16 with head_dim 64 or 128, k_stride_s must
- *               be a multiple of head_dim and n_hist * k_stride_s * 2 bytes < 2 GiB (else KRUL_EUNSUPPORTED).
+ *               k_stride_s >= head_dim (else KRUL_EINVAL); for bf16 / f16 with head_dim up to 128,
+ *               n_hist * k_stride_s * 2 bytes < 2 GiB and k_stride_s < 2^23 (else KRUL_EUNSUPPORTED).
  * The caller guarantees that every addressed key lies inside its layer's allocation.  Everything else
  * is as for krul_pair_similarity (same workspace size).
  */
@@ -165,8 +166,8 @@ int krul_pair_similarity_strided(const krul_shape_t *shape, const void *q, const
  *                elements between pages, kv heads and the keys of a page: key j of conversation b, kv head h starts
  *                at k_layers[l] + block_table[b][j / block_size]*k_stride_block + h*k_stride_h
  *                + (j % block_size)*k_stride_s; head_dim contiguous.  All > 0, multiples of 8, k_stride_s >=
- *                head_dim (else KRUL_EINVAL); for bf16 / f16 with head_dim 64 or 128, k_stride_s must be a multiple
- *                of head_dim below 2^27 (else KRUL_EUNSUPPORTED).  E.g. a [num_blocks][block_size][Hkv][d] pool:
+ *                head_dim (else KRUL_EINVAL); for bf16 / f16 with head_dim up to 128, k_stride_s < 2^27 (else
+ *                KRUL_EUNSUPPORTED).  E.g. a [num_blocks][block_size][Hkv][d] pool:
  *                (block_size*Hkv*d, d, Hkv*d).
  * Every page has room for block_size keys; the slots past the last key of a conversation may be read (their
  * contents do not matter, NaN included).

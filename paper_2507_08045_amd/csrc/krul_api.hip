@@ -45,7 +45,9 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
     y.n_layers = (int)L;
     y.rows_per_unit = (int)Rk;
 
-    const bool mfma = (s->dtype == KRUL_BF16 || s->dtype == KRUL_F16) && (s->head_dim == 64 || s->head_dim == 128) &&
+    // 16-bit inputs with a head size up to 128 take the matrix cores (64 and 128 as they are, the sizes between
+    // zero-padded to the next of the two inside LDS)
+    const bool mfma = (s->dtype == KRUL_BF16 || s->dtype == KRUL_F16) && s->head_dim <= 128 &&
                       !(s->flags & KRUL_FLAG_GENERIC_KERNEL);
     long long n_wg, records, spill_records = 0;
     if (mfma) {
@@ -150,9 +152,9 @@ int resolve_keys(const krul_shape_t *s, bool mfma, bool dense_2gib, const void *
         const long long sb = s->batch > 1 ? kl->k_stride_b : 8;   // (not used for one conversation)
         if (sb <= 0 || kl->k_stride_h <= 0 || kl->k_stride_s < d || ((sb | kl->k_stride_h | kl->k_stride_s) & 7))
             return KRUL_EINVAL;
-        // the matrix-core kernels' row swizzle needs whole head_dim multiples between keys; 32-bit
-        // offsets and ranges need a layer's keys of one head to span less than 2 GiB
-        if (mfma && (kl->k_stride_s % d != 0 || kl->k_stride_s >= (1ll << 23) ||
+        // the matrix-core kernels' 32-bit offsets and ranges need a layer's keys of one head to span
+        // less than 2 GiB
+        if (mfma && (kl->k_stride_s >= (1ll << 23) ||
                      (dense_2gib && kl->k_stride_s * 2 * S >= (1ll << 31))))
             return KRUL_EUNSUPPORTED;
         a.k_tab = kl->k_layers;
@@ -166,8 +168,8 @@ int resolve_keys(const krul_shape_t *s, bool mfma, bool dense_2gib, const void *
         if (bs < 8 || (bs & (bs - 1)) || kp->max_blocks < (S + bs - 1) / bs || kp->k_stride_block <= 0 ||
             kp->k_stride_h <= 0 || kp->k_stride_s < d || ((kp->k_stride_block | kp->k_stride_h | kp->k_stride_s) & 7))
             return KRUL_EINVAL;
-        // (row swizzle; 32-bit byte offsets over the keys one copy instruction moves)
-        if (mfma && (kp->k_stride_s % d != 0 || kp->k_stride_s >= (1ll << 27))) return KRUL_EUNSUPPORTED;
+        // (32-bit byte offsets over the keys one copy instruction moves)
+        if (mfma && kp->k_stride_s >= (1ll << 27)) return KRUL_EUNSUPPORTED;
         a.k_tab = kp->k_layers;
         a.block_table = kp->block_table;
         a.max_blocks = kp->max_blocks;

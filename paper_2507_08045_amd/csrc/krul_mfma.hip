@@ -13,7 +13,7 @@ hipError_t launch_sim_mfma_slim64(const SimParams &p, int n_workgroups, hipStrea
 
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
 {
-    const bool d128 = p.d == 128;
+    const bool d128 = p.d > 64;   // (head sizes below the kernel's ride in zero-padded LDS rows)
     switch (p.lay.variant) {
     case kMfmaWide:
     case kMfmaWideShort:

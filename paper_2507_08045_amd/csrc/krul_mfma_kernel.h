@@ -173,11 +173,18 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
     const uint16_t *Qg = static_cast<const uint16_t *>(p.q);
     const uint16_t *Kg = static_cast<const uint16_t *>(p.k);
-    const size_t q_layer_stride = (size_t)p.Hq * p.Tq * D;
+    constexpr bool SK = KA != 0;   // keys with strides, layers from a table
+    // Head size in memory: the kernel's D, or (SK) any multiple of 8 up to it.  Rows are copied piece by
+    // piece into the D-wide LDS rows; the pieces a shorter row does not have are left to lanes whose
+    // offset lies outside every range, which fetch nothing and write zero, so the MFMAs run over D as ever.
+    const int dq = SK ? p.d : D;
+    [[maybe_unused]] const unsigned d_bytes = (unsigned)dq * 2u;
+    [[maybe_unused]] const unsigned pp_real = (unsigned)dq >> 3;   // 16-byte pieces of a row in memory
+    constexpr unsigned kNoFetch = 0x7FFFFFF0u;
+    const size_t q_layer_stride = (size_t)p.Hq * p.Tq * dq;
     // Keys of layer l, this unit: k_layer(l) + k_tile_off, where k_tile_off leads to the unit's first key
     // of the tile being fetched (see SimParams).  Layer and tile advance by additions, so that the dense
     // layout costs no multiplications inside the loop.
-    constexpr bool SK = KA != 0;   // keys with strides, layers from a table
     const size_t k_stride_s = SK ? (size_t)p.k_stride_s : (size_t)D;
     // (paged: the page and the key inside it are added per copy instruction; only the head is fixed)
     size_t k_tile_off = KA == 2 ? (size_t)kvh * p.k_stride_h
@@ -188,9 +195,10 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         // the table is read as constant memory at a uniform address: a scalar load, which takes no place in
         // the vector-memory queue that the ring's waits count
         typedef const __attribute__((address_space(4))) unsigned long long *const_u64_ptr;
-        return SK ? (const uint16_t *)(uintptr_t)((const_u64_ptr)(uintptr_t)p.k_tab)[l] : k_dense;
+        // (SK without a table: the dense layout with a head size below D)
+        return SK && p.k_tab ? (const uint16_t *)(uintptr_t)((const_u64_ptr)(uintptr_t)p.k_tab)[l] : k_dense;
     };
-    const unsigned k_row_bytes = (unsigned)k_stride_s * 2u;   // a multiple of 2*D: the swizzle bits stay clear
+    const unsigned k_row_bytes = (unsigned)k_stride_s * 2u;   // (dense: 2*D, the swizzle bits stay clear)
     const unsigned k_chunk_bytes = (unsigned)C::CH * k_row_bytes;   // (a layer's keys of one head span < 2 GiB)
 
     // ---- direct-to-LDS copies.  One wave-instruction moves 1 KB = RPI whole rows: the lane
@@ -203,18 +211,23 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
 
     // K ring: wave-instruction j of this wave fills granules [(wave*NLD+j)*64, +64) of a slot.
     const int ld_row0 = wave * NLD * RPI + lane / PPR;
-    const unsigned ld_off0 = (unsigned)ld_row0 * k_row_bytes + (unsigned)(((lane % PPR) ^ swz<D>(ld_row0)) * 16);
+    [[maybe_unused]] const unsigned ld_off0 = (unsigned)ld_row0 * k_row_bytes + (unsigned)(((lane % PPR) ^ swz<D>(ld_row0)) * 16);
     // The chunk copied during chunk c of a step is chunk c of the NEXT step (PF + 1 = NC chunks
     // later), so per step one base address serves all its copies: that of the next step's
     // layer and key tile (fetch_k), with the tile's first key (fetch_key0).
     const uint16_t *fetch_k = uniform_ptr(k_layer(0) + k_tile_off);
     int fetch_key0 = key_begin;
+    // SK: the lane offset of copy instruction j, worked out piece by piece (any row pitch, any head size):
+    // the lane's LDS granule holds piece pj of its row, if the row has it
+    [[maybe_unused]] auto k_lane_off = [&](int j, unsigned row_off) -> unsigned {
+        const unsigned pj = (unsigned)((lane % PPR) ^ swz<D>(ld_row0)) ^ (xj(j) >> 4);
+        return pj < pp_real ? row_off + pj * 16u : kNoFetch;
+    };
     // Paged keys: a copy instruction moves RPI whole keys, which lie in one page (pages hold a power of
     // two >= 8 keys and tiles start on multiples of them); its page comes from the conversation's block
     // table by a scalar load, and it gets a descriptor of its own, bounded by the keys that exist.
     // (On this chip the scalar offset of a buffer instruction takes part in the range check, like the
     // lane offset: the dense path below relies on that.)
-    const unsigned ld_offp = (unsigned)(lane / PPR) * k_row_bytes + (unsigned)(((lane % PPR) ^ swz<D>(ld_row0)) * 16);
     typedef const __attribute__((address_space(4))) int *const_i32_ptr;
     const const_i32_ptr page_row = KA == 2 ? (const_i32_ptr)(uintptr_t)(p.block_table + (size_t)b * p.max_blocks) : nullptr;
     // Where each copy instruction of a tile starts, relative to the layer's pool (wave-uniform, in scalar
@@ -235,7 +248,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         }
     };
     load_pages(key_begin);
-    const unsigned page_copy_bytes = (unsigned)(RPI - 1) * k_row_bytes + (unsigned)(D * 2);
+    const unsigned page_copy_bytes = (unsigned)(RPI - 1) * k_row_bytes + d_bytes;
     auto issue_chunk = [&](int c, bool live) __attribute__((always_inline)) {
         unsigned char *dst = slot_ptr(c);
         const int key0 = fetch_key0 + c * C::CH;
@@ -254,21 +267,22 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                     __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     rsrc, (__attribute__((address_space(3))) void *)(dst + (wave * NLD + j) * 1024), 16,
-                    (int)(ld_offp ^ xj(j)), 0, 0, 0);
+                    (int)k_lane_off(j, (unsigned)(lane / PPR) * k_row_bytes), 0, 0, 0);
             }
             return;
         }
         // Buffer addressing: a scalar descriptor for the rest of this layer's keys (rows past
         // the last key are out of range and are not fetched), one 32-bit offset per lane.
         // (a chunk past the end of the split gets an empty range: nothing is fetched)
-        const unsigned bytes = live && key0 < S ? (unsigned)(S - key0 - 1) * k_row_bytes + (unsigned)(D * 2) : 0u;
+        const unsigned bytes = live && key0 < S ? (unsigned)(S - key0 - 1) * k_row_bytes + (SK ? d_bytes : (unsigned)(D * 2)) : 0u;
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint16_t *>(fetch_k + (c * k_chunk_bytes) / 2), 0, (int)bytes, 0x00020000);
 #pragma unroll
         for (int j = 0; j < NLD; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rsrc, (__attribute__((address_space(3))) void *)(dst + (wave * NLD + j) * 1024), 16,
-                (int)(ld_off0 ^ xj(j)), (int)(j * RPI * k_row_bytes), 0, 0);
+                SK ? (int)k_lane_off(j, (unsigned)ld_row0 * k_row_bytes) : (int)(ld_off0 ^ xj(j)),
+                (int)(j * RPI * k_row_bytes), 0, 0);
     };
 
     // Query rows: the 32 rows of wave row wr are staged in LDS (laid out like a 32-key block)
@@ -277,20 +291,29 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     // fetched, their results are never read back.
     const int r0 = rt * C::R_WG + wr * 32;
     const int q_rows = min(max(Rk - r0, 0), 32);
-    const uint16_t *qbase = uniform_ptr(Qg + ((size_t)b * L * p.Hq * p.Tq + (size_t)kvh * Rk + (size_t)(q_rows ? r0 : 0)) * D);
-    const unsigned q_off0 = (unsigned)((lane / PPR) * (D * 2) + (((lane % PPR) ^ swz<D>(lane / PPR)) * 16));
+    const uint16_t *qbase = uniform_ptr(Qg + ((size_t)b * L * p.Hq * p.Tq + (size_t)kvh * Rk + (size_t)(q_rows ? r0 : 0)) * dq);
+    [[maybe_unused]] const unsigned q_off0 = (unsigned)((lane / PPR) * (D * 2) + (((lane % PPR) ^ swz<D>(lane / PPR)) * 16));
     const uint16_t *fetch_q = qbase;   // query rows of the next step's layer
     auto issue_q = [&](bool live) __attribute__((always_inline)) {
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint16_t *>(fetch_q), 0, __builtin_amdgcn_readfirstlane(live ? q_rows * (D * 2) : 0), 0x00020000);
+            const_cast<uint16_t *>(fetch_q), 0, __builtin_amdgcn_readfirstlane(live ? q_rows * (int)(SK ? d_bytes : (unsigned)(D * 2)) : 0), 0x00020000);
         unsigned char *dst = qlds + wr * C::QBYTES;
 #pragma unroll
         for (int jj = 0; jj < C::QPW; ++jj) {
             const int j = wk * C::QPW + jj;
-            if (j < C::NQI)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    rsrc, (__attribute__((address_space(3))) void *)(dst + j * 1024), 16,
-                    (int)(q_off0 ^ xj(j)), j * 1024, 0, 0);
+            if (j < C::NQI) {
+                if constexpr (SK) {   // piece by piece, as for the keys
+                    const unsigned pj = (unsigned)((lane % PPR) ^ swz<D>(lane / PPR)) ^ (xj(j) >> 4);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        rsrc, (__attribute__((address_space(3))) void *)(dst + j * 1024), 16,
+                        (int)(pj < pp_real ? (unsigned)(lane / PPR) * d_bytes + pj * 16u : kNoFetch),
+                        (int)((unsigned)(j * RPI) * d_bytes), 0, 0);
+                } else {
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        rsrc, (__attribute__((address_space(3))) void *)(dst + j * 1024), 16,
+                        (int)(q_off0 ^ xj(j)), j * 1024, 0, 0);
+                }
+            }
         }
     };
 
@@ -622,7 +645,8 @@ template <class C, bool F16>
 hipError_t launch_cfg_t(const SimParams &p, int n_workgroups, hipStream_t st)
 {
     if (p.block_table) return launch_mode<C, 2, F16>(p, n_workgroups, st);   // keys in pages
-    if (p.k_tab) return launch_mode<C, 1, F16>(p, n_workgroups, st);         // keys in per-layer allocations, with strides
+    // keys in per-layer allocations, with strides -- or dense, with a head size below the kernel's
+    if (p.k_tab || p.d != C::D) return launch_mode<C, 1, F16>(p, n_workgroups, st);
     return launch_mode<C, 0, F16>(p, n_workgroups, st);
 }
 

@@ -145,7 +145,7 @@ def test_strided_entry_point_rejects_bad_arguments_before_any_gpu_work(kr):
     assert call(sh=-128) == kr.KRUL_EINVAL
     assert call(ss=64) == kr.KRUL_EINVAL               # keys would overlap
     assert call(ss=132) == kr.KRUL_EINVAL              # not a multiple of 8 elements
-    assert call(ss=136) == kr.KRUL_EUNSUPPORTED        # bf16 kernel: whole head_dims between keys
+    assert call(ss=136, ws_bytes=16) == kr.KRUL_EWORKSPACE   # any multiple of 8 elements between keys will do
     assert call(ss=1 << 23) == kr.KRUL_EUNSUPPORTED    # 256 keys * 16 MiB: beyond the 32-bit key offsets
     assert call(shape(kr, B=2, flags=kr.KRUL_FLAG_GENERIC_KERNEL), ss=136, ws_bytes=16) == kr.KRUL_EWORKSPACE
     assert call(shape(kr, B=1), sb=0, ws_bytes=16) == kr.KRUL_EWORKSPACE   # one conversation: k_stride_b unused
@@ -170,7 +170,8 @@ def test_paged_entry_point_rejects_bad_arguments_before_any_gpu_work(kr):
     assert call(mb=15) == kr.KRUL_EINVAL                # 256 keys need 16 pages of 16
     assert call(sp=0) == kr.KRUL_EINVAL
     assert call(ss=64) == kr.KRUL_EINVAL                # keys would overlap
-    assert call(ss=136) == kr.KRUL_EUNSUPPORTED         # bf16 kernel: whole head_dims between keys
+    assert call(ss=136, ws_bytes=16) == kr.KRUL_EWORKSPACE    # any multiple of 8 elements between keys will do
+    assert call(ss=1 << 27) == kr.KRUL_EUNSUPPORTED     # beyond the 32-bit offsets inside one copy
     assert call(shape(kr, B=2, flags=kr.KRUL_FLAG_GENERIC_KERNEL), ss=136, ws_bytes=16) == kr.KRUL_EWORKSPACE
     assert call(ws_bytes=16) == kr.KRUL_EWORKSPACE
 
