@@ -305,7 +305,7 @@ int krul_pair_similarity_select(const krul_shape_t *shape, const void *q, const 
  *                   less than the bytes for the smallest batch, up to 256 rows of one kv head), or 0 if the
  *                   shape is not supported.  Any size from the smallest batch's up is accepted by the
  *                   call; more memory means fewer, larger launches.
- * Limits: n_layers <= 128.  bf16 or f16 with head_dim 64 or 128 runs on the matrix cores; other inputs take a
+ * Limits: n_layers <= 128.  bf16 or f16 with head_dim up to 128 runs on the matrix cores; other inputs take a
  * portable, slow kernel.  Exponentials are rounded to fp16 (2^-11 relative) before the products.
  * Results are deterministic.  Errors as for krul_pair_similarity.
  */

@@ -141,10 +141,16 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
     typedef const __attribute__((address_space(4))) unsigned long long *const_u64_ptr;   // constant memory: scalar loads
     typedef const __attribute__((address_space(4))) int *const_i32_ptr;
     [[maybe_unused]] const uint16_t *klayer =
-        INPLACE ? (const uint16_t *)(uintptr_t)((const_u64_ptr)(uintptr_t)p.ka.k_tab)[l] + (size_t)kvh * p.ka.stride_h +
-                      (p.ka.block_table ? 0 : (size_t)b * p.ka.stride_b)
+        INPLACE ? (p.ka.k_tab ? (const uint16_t *)(uintptr_t)((const_u64_ptr)(uintptr_t)p.ka.k_tab)[l]
+                              : static_cast<const uint16_t *>(p.ka.k) + (size_t)l * p.ka.stride_l) +   // (dense, head size below D)
+                      (size_t)kvh * p.ka.stride_h + (p.ka.block_table ? 0 : (size_t)b * p.ka.stride_b)
                 : static_cast<const uint16_t *>(p.k) + ((((size_t)b * p.L + l) * p.Hkv + kvh) * (size_t)S) * D;
     [[maybe_unused]] const unsigned k_row_bytes = INPLACE ? (unsigned)p.ka.stride_s * 2u : (unsigned)ROWB;
+    // head size in memory (INPLACE: any multiple of 8 up to D; the pieces a shorter row does not have are left
+    // to lanes whose offset lies past every range: they fetch nothing and write zero)
+    [[maybe_unused]] const int dq = INPLACE ? p.d : D;
+    [[maybe_unused]] const unsigned d_bytes = (unsigned)dq * 2u, pp_real = (unsigned)dq >> 3;
+    constexpr unsigned kNoFetch = 0x7FFFFFF0u;
     // The keys go HBM -> LDS directly (buffer_load ... lds, no staging registers):
     // wave-instruction j fills the 1 KB at j*1024 (RPI key rows), lane by lane, so each lane fetches
     // the 16-byte piece that belongs at its LDS position (the XOR swizzle applied on the global
@@ -165,13 +171,14 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
                     const int krow = t * KR + j * RPI, kcl = min(krow, S - 1);
                     const uint16_t *base = klayer + (size_t)page_row[kcl >> p.ka.page_shift] * p.ka.stride_page +
                                            (size_t)(kcl & ((1 << p.ka.page_shift) - 1)) * p.ka.stride_s;
-                    const unsigned bytes = krow < S ? (unsigned)(RPI - 1) * k_row_bytes + (unsigned)ROWB : 0u;
+                    const unsigned bytes = krow < S ? (unsigned)(RPI - 1) * k_row_bytes + d_bytes : 0u;
                     const __amdgpu_buffer_rsrc_t rsrc =
                         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
-                    const int row = j * RPI + lane / PPR, pos = lane % PPR;
+                    const int row = j * RPI + lane / PPR;
+                    const unsigned pj = (unsigned)((lane % PPR) ^ swz<D>(row));
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(
                         rsrc, (__attribute__((address_space(3))) void *)(&kl[buf][0] + j * 1024), 16,
-                        (int)((unsigned)(lane / PPR) * k_row_bytes + (unsigned)((pos ^ swz<D>(row)) << 4)), 0, 0, 0);
+                        (int)(pj < pp_real ? (unsigned)(lane / PPR) * k_row_bytes + (pj << 4) : kNoFetch), 0, 0, 0);
                 }
             } else {
                 // strides: one descriptor for the split, the row pitch a run-time value
@@ -180,14 +187,15 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
                                                           (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)ka));
                 const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
                     const_cast<uint16_t *>(kb_u), 0,
-                    __builtin_amdgcn_readfirstlane(kn > 0 ? (int)((unsigned)(kn - 1) * k_row_bytes + (unsigned)ROWB) : 0), 0x00020000);
+                    __builtin_amdgcn_readfirstlane(kn > 0 ? (int)((unsigned)(kn - 1) * k_row_bytes + d_bytes) : 0), 0x00020000);
 #pragma unroll
                 for (int jj = 0; jj < NI; ++jj) {
                     const int j = __builtin_amdgcn_readfirstlane(w) * NI + jj;
-                    const int row = j * RPI + lane / PPR, pos = lane % PPR;
+                    const int row = j * RPI + lane / PPR;
+                    const unsigned pj = (unsigned)((lane % PPR) ^ swz<D>(row));
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(
                         rsrc, (__attribute__((address_space(3))) void *)(&kl[buf][0] + j * 1024), 16,
-                        (int)((unsigned)row * k_row_bytes + (unsigned)((pos ^ swz<D>(row)) << 4)), 0, 0, 0);
+                        (int)(pj < pp_real ? (unsigned)row * k_row_bytes + (pj << 4) : kNoFetch), 0, 0, 0);
                 }
             }
             return;
@@ -214,11 +222,11 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void ap_weights_mfma_kern
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
         const int r = ((rg * NW + w) * RB + j) * 32 + n;
-        const uint16_t *qrow = Qg + ((((size_t)b * p.L + l) * p.Hq + (size_t)kvh * p.g) * p.Tq + (size_t)(row_ok[j] ? r : 0)) * D;
+        const uint16_t *qrow = Qg + ((((size_t)b * p.L + l) * p.Hq + (size_t)kvh * p.g) * p.Tq + (size_t)(row_ok[j] ? r : 0)) * dq;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (row_ok[j]) v = *reinterpret_cast<const uint4 *>(qrow + ks * 16 + half * 8);
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);   // (zero: rows that do not exist, elements past the head size)
+            if (row_ok[j] && ks * 16 + half * 8 < dq) v = *reinterpret_cast<const uint4 *>(qrow + ks * 16 + half * 8);
             qf[j][ks] = __builtin_bit_cast(bf16x8, v);
         }
     }
@@ -896,7 +904,7 @@ int ap_plan(const krul_shape_t *s, size_t max_bytes, APPlan *pl)
     const long long total = (long long)s->batch * s->n_kv_heads * pl->NRG;
     if (total * pl->NW * 32 > INT32_MAX / 4) return KRUL_EUNSUPPORTED;
     pl->total_rg = (int)total;
-    pl->mfma = (s->dtype == KRUL_BF16 || s->dtype == KRUL_F16) && (s->head_dim == 64 || s->head_dim == 128) &&
+    pl->mfma = (s->dtype == KRUL_BF16 || s->dtype == KRUL_F16) && s->head_dim <= 128 &&
                !(s->flags & KRUL_FLAG_GENERIC_KERNEL);
     // key splits of the weights kernel: one per kKeysPerSplit keys (the portable kernel does not split)
     if (pl->mfma) {
@@ -930,7 +938,7 @@ template <int D, bool F16>
 void launch_weights(const APParams &p, hipStream_t st)
 {
     const dim3 grid(p.nrg * p.L * ((p.nsplit + p.tpw - 1) / p.tpw));
-    if (p.ka.k_tab) {
+    if (p.ka.k_tab || p.d != D) {
         switch (p.NW) {
         case 1: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 1, 1, F16, true>), grid, dim3(64), 0, st, p); break;
         case 2: hipLaunchKernelGGL((ap_weights_mfma_kernel<D, 2, 1, F16, true>), grid, dim3(128), 0, st, p); break;
@@ -1023,7 +1031,7 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, const kru
         const int rblocks = p.nrg * p.NW, rows = rblocks * 32;
         if (pl.mfma) {
             const bool f16 = s->dtype == KRUL_F16;
-            if (p.d == 128)
+            if (p.d > 64)   // (head sizes below the kernel's ride zero-padded in LDS: the in-place form)
                 f16 ? launch_weights<128, true>(p, st) : launch_weights<128, false>(p, st);
             else
                 f16 ? launch_weights<64, true>(p, st) : launch_weights<64, false>(p, st);

@@ -74,6 +74,14 @@ def test_head_sizes_match_oracle(G, oracle, case):
         gc = kr.pair_similarity(q, k, flags=kr.KRUL_FLAG_CAUSAL)
         torch.cuda.synchronize()
         G.assert_close(gc["head_score"].cpu().numpy(), wantc["head_score"], G.TOL, f"{name} causal")
+    # every two layers, from dense keys and out of the pages
+    want_ap = oracle.all_pairs(w.q, w.k)
+    ap = kr.all_pairs_similarity(q, k, want_head_score=True)
+    ap_paged = kr.all_pairs_similarity_in_place(q, kr.PagedKeys(pools, table, S), want_head_score=True)
+    torch.cuda.synchronize()
+    G.assert_close(ap["head_score"].cpu().numpy(), want_ap["head_score"], G.TOL, f"{name} all-pairs head_score")
+    G.assert_close(ap["pair_dist"].cpu().numpy(), want_ap["pair_dist"], G.TOL, f"{name} all-pairs pair_dist")
+    np.testing.assert_array_equal(ap_paged["head_score"].cpu().numpy(), ap["head_score"].cpu().numpy())
     del keep_s, keep_p
 
 
