@@ -1018,9 +1018,9 @@ int run_all_pairs(const krul_shape_t *s, const void *q, const void *k, const kru
 
     const int L = p.L, LL = L * L;
     const size_t n_head = (size_t)p.B * p.Hq * kClasses * LL;
-    hipLaunchKernelGGL(ap_fill_kernel, dim3((unsigned)((n_head + 255) / 256)), dim3(256), 0, st, p.head_cos, n_head, 0.f);
-    if (p.want_dist)
-        hipLaunchKernelGGL(ap_fill_kernel, dim3((unsigned)((n_head + 255) / 256)), dim3(256), 0, st, p.head_dist, n_head, 0.f);
+    // (the two areas of running sums lie one after the other in the workspace: one launch clears both)
+    const size_t n_fill = p.want_dist ? (size_t)(p.head_dist - p.head_cos) + n_head : n_head;
+    hipLaunchKernelGGL(ap_fill_kernel, dim3((unsigned)((n_fill + 255) / 256)), dim3(256), 0, st, p.head_cos, n_fill, 0.f);
     if (hipGetLastError() != hipSuccess) return KRUL_ELAUNCH;
 
     const int NB = (L + 31) / 32, NACC = NB * (NB + 1) / 2;
