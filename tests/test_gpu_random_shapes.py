@@ -20,7 +20,7 @@ def G():
 def draw(rng):
     """One case: shape, storage type, flags and which call takes it."""
     while True:
-        c = dict(dtype=str(rng.choice(["bf16", "bf16", "f16", "f32"])), d=int(rng.choice([64, 128, 128, 32, 96])),
+        c = dict(dtype=str(rng.choice(["bf16", "bf16", "f16", "f32"])), d=int(rng.choice([8, 24, 40, 56, 64, 72, 96, 112, 128, 128, 136])),
                  Hkv=int(rng.choice([1, 2, 4, 8])), g=int(rng.choice([1, 2, 4, 8])),
                  Tq=int(rng.choice([1, 1, 2, 3, 5, 8, 9, 16, 17, 33, 64, 70, 130])),
                  S=int(rng.choice([1, 7, 31, 33, 64, 100, 129, 255, 257, 500, 700, 1025, 1500, 2100])),
