@@ -41,32 +41,39 @@ def algorithmic_valu_ops(w, with_dist=False) -> int:
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
-def cpu_baseline(w, seconds_target=15.0):
-    """The fp64 oracle, as it stands, on a bounded sample of (b, pair, head) units."""
+def cpu_baseline(w, q, k, seconds_target=15.0):
+    """The fp64 oracle, as it stands, on a bounded seeded sample of (conversation, pair, head) units -- all query
+    rows and all keys of each -- copied back from the device tensors the GPU path read.  Work is linear in units,
+    so the figure is the sample's own rate (score-elems of the sample / wall time)."""
     import numpy as np
     import oracle
+    import workloads
     oracle.build()
     n_all = w.B * (w.L - 1) * w.Hq
     rng = np.random.default_rng(12345)
-    all_units = [(b, l, h) for b in range(w.B) for l in range(w.L - 1) for h in range(w.Hq)]
     threads = oracle.num_threads()
-    # calibrate on one unit per thread, then size the sample for ~seconds_target
-    probe = [all_units[i] for i in rng.choice(n_all, size=min(threads, n_all), replace=False)]
-    t0 = time.perf_counter()
-    oracle.unit_scores(w.q, w.k, probe)
-    t_probe = time.perf_counter() - t0
+
+    def draw(n):
+        idx = rng.choice(n_all, size=min(n, n_all), replace=False)
+        return [(int(i // ((w.L - 1) * w.Hq)), int(i // w.Hq % (w.L - 1)), int(i % w.Hq)) for i in idx]
+
+    def run(units):
+        qs, ks = workloads.units_to_host(q, k, units)
+        t0 = time.perf_counter()
+        oracle.pair_similarity(qs, ks)
+        return time.perf_counter() - t0
+
+    # calibrate on one unit per thread, then size the sample for about seconds_target
+    t_probe = run(draw(threads))
     n = int(min(n_all, max(threads, threads * (seconds_target / max(t_probe, 1e-3)))))
-    n = max(threads, n // threads * threads)
-    n = min(n, n_all)
-    sample = [all_units[i] for i in rng.choice(n_all, size=n, replace=False)]
-    t0 = time.perf_counter()
-    oracle.unit_scores(w.q, w.k, sample)
-    dt = time.perf_counter() - t0
+    n = min(max(threads, n // threads * threads), n_all, 4096)
+    dt = run(draw(n))
     elems = n * w.Tq * w.S
     return {
         "value": elems / dt / 1e9, "unit": "Gscore-elems/s", "cores": threads, "kind": "oracle",
-        "sample": f"{n} of {n_all} (conversation, pair, head) units of {w.name}, all rows and keys, "
-                  f"{dt:.1f} s wall",
+        "sample": f"{n} of {n_all} (conversation, pair, head) units of {w.name}, all rows and keys of each, "
+                  f"{dt:.1f} s wall; the whole workload extrapolated from these n units: "
+                  f"{dt * n_all / n:.0f} s",
     }
 
 
@@ -91,9 +98,10 @@ def all_pairs_bench(args, kr, torch, w, q, k, shp):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     gpu_s = e0.elapsed_time(e1) * 1e-3 / args.steps
-    esz = 2 if w.dtype == "bf16" else 4
-    in_bytes = (w.q.size + w.k.size) * esz
+    in_bytes = (q.numel() + k.numel()) * q.element_size()
+    out_bytes = 2 * w.B * w.L * w.L * 4
     weights_bytes = w.B * w.Hq * w.Tq * w.L * ((w.S + 31) // 32 * 32) * 2   # fp16 attention weights, written once, read once
+    design_bytes = in_bytes + 2 * weights_bytes
     res = {
         "metric": "all-pairs layer similarity throughput", "value": w.score_elems / (dt / args.steps) / 1e9,
         "unit": "Gscore-elems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -102,24 +110,59 @@ def all_pairs_bench(args, kr, torch, w, q, k, shp):
         "config": {"workload": f"{w.name}: B={w.B} L={w.L} Hq/Hkv={w.Hq}/{w.Hkv} d={w.d} S={w.S} Tq={w.Tq} "
                                f"{w.dtype}, all {w.L * (w.L - 1) // 2} layer pairs, select {w.n_select}",
                    "score_elems": w.score_elems, "outputs": "pair_score_all+pair_dist_all", "workspace_bytes": ws.numel()},
-        # the design's own traffic: inputs once, the fp16 weights out and back
-        "roofline": {"bound": "hbm", "achieved": (in_bytes + 2 * weights_bytes) / gpu_s / 1e9, "peak": 8000.0,
-                     "unit": "GB/s", "frac": (in_bytes + 2 * weights_bytes) / gpu_s / 1e9 / 8000.0, "traffic": None,
+        # against the algorithmic bytes (inputs once, outputs once); what this design moves on top of them -- the
+        # fp16 attention weights out to HBM and back -- is given as design_traffic, and its ratio to the
+        # algorithmic bytes says how far the path is from a fused one
+        "roofline": {"bound": "hbm", "achieved": (in_bytes + out_bytes) / gpu_s / 1e9, "peak": 8000.0,
+                     "unit": "GB/s", "frac": (in_bytes + out_bytes) / gpu_s / 1e9 / 8000.0, "traffic": None,
                      "kernel": "whole call (weights, scale, Gram, row, reduce kernels)", "kernel_us": gpu_s * 1e6,
-                     "algorithmic_bytes": in_bytes + 2 * weights_bytes, "input_bytes": in_bytes},
+                     "algorithmic_bytes": in_bytes + out_bytes, "design_traffic": design_bytes,
+                     "design_traffic_over_algorithmic": design_bytes / (in_bytes + out_bytes),
+                     "design_traffic_frac_of_peak": design_bytes / gpu_s / 1e9 / 8000.0},
         "selected_pairs": pairs.cpu().tolist()[0],
     }
     print(json.dumps(res))
 
 
+class _Shape:
+    """Extents and names of the workload being timed (the numbers live in the device tensors)."""
+    def __init__(self, **kw):
+        self.__dict__.update(kw)
+        self.score_elems = self.B * (self.L - 1) * self.Hq * self.Tq * self.S
+
+
+def load_inputs(name, torch, np):
+    """(shape, [(q, k), ...]): the configuration's inputs on the device.  C5 (22.5 GiB) is drawn on the device;
+    the others on the host, as the parity tests draw them.  Inputs smaller than twice the 256 MB last-level cache
+    are held in two copies at different addresses and the steps alternate between them, so that no step finds
+    the inputs of the step before it in that cache."""
+    import workloads
+    if name == "C5":
+        q, k, info = workloads.config_device(name)
+        w = _Shape(**{f: info[f] for f in ("name", "B", "L", "Hq", "Hkv", "d", "S", "Tq", "dtype", "n_select")})
+        return w, [(q, k)]
+    ww = workloads.config(name)
+    w = _Shape(**{f: getattr(ww, f) for f in ("name", "B", "L", "Hq", "Hkv", "d", "S", "Tq", "dtype", "n_select")})
+    if ww.dtype == "f32":
+        q, k = torch.from_numpy(ww.q).cuda(), torch.from_numpy(ww.k).cuda()
+    else:
+        q = torch.from_numpy(ww.q.view(np.int16)).cuda().view(torch.bfloat16)
+        k = torch.from_numpy(ww.k.view(np.int16)).cuda().view(torch.bfloat16)
+    sets = [(q, k)]
+    if (q.numel() + k.numel()) * q.element_size() < 2 * 256e6:
+        sets.append((q.clone(), k.clone()))
+    return w, sets
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "D1", "D2", "D3"],
-                    help="C5 draws 22.5 GiB of inputs on the host first (minutes); give it few --steps.  D1..D3 are "
-                         "decode-step shapes (one query token), not among the benchmark's configurations")
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C5", choices=["C1", "C2", "C3", "C4", "C5", "D1", "D2", "D3"],
+                    help="C5 (the default; the largest configuration that fits one GPU) draws its 22.5 GiB of inputs on "
+                         "the device.  D1..D3 are decode-step shapes (one query token), not among the benchmark's "
+                         "configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--with-dist", action="store_true",
@@ -144,19 +187,15 @@ def main():
 
     import paper_2507_08045_amd as kr
     from paper_2507_08045_amd import hipevents
-    import workloads
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    w = workloads.config(args.config, progress=lambda b, n: print(f"bench.py: drew conversation {b + 1} of {n}",
-                                                                    file=sys.stderr, flush=True) if args.config == "C5" else None)
-    if w.dtype == "f32":
-        q, k = torch.from_numpy(w.q).cuda(), torch.from_numpy(w.k).cuda()
-    else:
-        q = torch.from_numpy(w.q.view(np.int16)).cuda().view(torch.bfloat16)
-        k = torch.from_numpy(w.k.view(np.int16)).cuda().view(torch.bfloat16)
+    w, sets = load_inputs(args.config, torch, np)
+    q, k = sets[0]
+    torch.cuda.synchronize()
+    print(f"bench.py: inputs of {w.name} on the device ({len(sets)} buffer set(s))", file=sys.stderr, flush=True)
 
     shp = kr.make_shape(q, k, 0.0, args.flags)
     if args.all_pairs:
@@ -172,29 +211,30 @@ def main():
     pairs = torch.empty((w.B, w.n_select), dtype=torch.int32, device="cuda")
     count = torch.empty((w.B,), dtype=torch.int32, device="cuda")
     K = args.steps
-    # The similarity kernel is timed with HIP events on a sample of the timed steps (every
-    # EV_EVERY-th): an event pair costs a few microseconds of stream time, which at this step
-    # length would distort the step time it is measured within.
+    # The similarity kernel is timed with HIP events (on the stream the library launches on) on a sample of
+    # the timed steps: an event pair costs a few microseconds of stream time, which for a step of a hundred
+    # microseconds would distort the step time it is measured within.
     EV_EVERY = 4 if K >= 16 else 1
     evs = [(hipevents.create(), hipevents.create()) if i % EV_EVERY == 0 else None for i in range(K)]
 
     out_sel = dict(out, pairs=pairs, count=count)
 
-    def step(ev=None):
+    def step(i, ev=None):
+        qi, ki = sets[i % len(sets)]
         if args.two_calls:
-            kr.pair_similarity(q, k, flags=args.flags, workspace=ws, out=out, events=ev,
+            kr.pair_similarity(qi, ki, flags=args.flags, workspace=ws, out=out, events=ev,
                                want_pair_dist=args.with_dist)
             kr.select_pairs(out["pair_score"], w.n_select, out_pairs=pairs, out_count=count)
         else:   # the same two steps of Alg. 1 through the entry point that enqueues both
-            kr.pair_similarity_select(q, k, w.n_select, flags=args.flags, workspace=ws, out=out_sel, events=ev,
+            kr.pair_similarity_select(qi, ki, w.n_select, flags=args.flags, workspace=ws, out=out_sel, events=ev,
                                       want_pair_dist=args.with_dist)
 
-    for _ in range(args.warmup):
-        step()
+    for i in range(args.warmup):
+        step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        step(evs[i])
+        step(i, evs[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -215,13 +255,30 @@ def main():
     value = w.score_elems / (dt / K) / 1e9
 
     bytes_alg, flops_alg = algorithmic_bytes(w), algorithmic_flops(w)
-    traffic = None
+    valu_alg = algorithmic_valu_ops(w, args.with_dist)
+    # HBM bytes per launch by rocprofv3 counters: recorded by an earlier profiling run of this library (the file
+    # names its command), not measured by this run
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
-    hbm_gbs = bytes_alg / kern_s / 1e9
-    mfma_tflops = flops_alg / kern_s / 1e12
+        traffic_src = f"profiles/traffic_{w.name}.json (recorded by a rocprofv3 --pmc run, not by this run)"
+    kernel_name = "sim_mfma_kernel" if w.dtype == "bf16" and not (args.flags & 256) else "sim_generic_kernel"
+    hbm = {"bound": "hbm", "achieved": bytes_alg / kern_s / 1e9, "peak": 8000.0, "unit": "GB/s",
+           "frac": bytes_alg / kern_s / 1e9 / 8000.0, "algorithmic_bytes": bytes_alg}
+    mfma = {"bound": "mfma", "achieved": flops_alg / kern_s / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+            "frac": flops_alg / kern_s / 1e12 / 2500.0, "algorithmic_flops": flops_alg}
+    alu = {"bound": "alu", "achieved": valu_alg / kern_s / 1e12, "peak": VALU_PEAK_TOPS, "unit": "T lane-op/s",
+           "frac": valu_alg / kern_s / 1e12 / VALU_PEAK_TOPS, "algorithmic_lane_ops": valu_alg}
+    # The roof that binds this workload: the one whose floor time (algorithmic work / peak) is longest.  The matrix
+    # cores bind the many-query configurations (C4, C5), the HBM stream of keys the few-query ones (C2, C3, D*);
+    # the vector units' floor is reported beside them (matrix and vector instructions share a wave's issue slots).
+    main_roof = dict(mfma if w.dtype == "bf16" and flops_alg / 2500e12 > bytes_alg / 8000e9 else hbm)
+    main_roof.update({"traffic": traffic, "traffic_source": traffic_src, "kernel": kernel_name,
+                      "kernel_us": kern_s * 1e6, "kernel_us_samples": len(kern_ms),
+                      "floor_us": {"hbm": bytes_alg / 8000e9 * 1e6, "mfma": flops_alg / 2500e12 * 1e6,
+                                   "alu": valu_alg / (VALU_PEAK_TOPS * 1e12) * 1e6}})
     res = {
         "metric": "layer-pair similarity throughput", "value": value, "unit": "Gscore-elems/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -230,22 +287,14 @@ def main():
         "config": {"workload": f"{w.name}: B={w.B} L={w.L} Hq/Hkv={w.Hq}/{w.Hkv} d={w.d} S={w.S} Tq={w.Tq} "
                                f"{w.dtype}, select {w.n_select} pairs", "score_elems": w.score_elems,
                    "outputs": "pair_score+head_score" + ("+pair_dist" if args.with_dist else "") + "+pairs",
-                   "calls": "krul_pair_similarity + krul_select_pairs" if args.two_calls else "krul_pair_similarity_select"},
-        "roofline": {"bound": "hbm", "achieved": hbm_gbs, "peak": 8000.0, "unit": "GB/s",
-                     "frac": hbm_gbs / 8000.0, "traffic": traffic,
-                     "kernel": "sim_mfma_kernel" if w.dtype == "bf16" and not (args.flags & 256) else "sim_generic_kernel",
-                     "kernel_us": kern_s * 1e6, "kernel_us_samples": len(kern_ms), "algorithmic_bytes": bytes_alg},
-        "roofline_mfma": {"bound": "mfma", "achieved": mfma_tflops, "peak": 2500.0, "unit": "TFLOP/s",
-                          "frac": mfma_tflops / 2500.0, "algorithmic_flops": flops_alg},
-        # the matrix and the vector instructions of a wave share its issue slots and overlap only partly, so
-        # the kernel's compute floor is close to the SUM of these two fractions, not their maximum
-        "roofline_alu": {"bound": "alu", "achieved": algorithmic_valu_ops(w, args.with_dist) / kern_s / 1e12,
-                         "peak": VALU_PEAK_TOPS, "unit": "T lane-op/s",
-                         "frac": algorithmic_valu_ops(w, args.with_dist) / kern_s / 1e12 / VALU_PEAK_TOPS},
+                   "calls": "krul_pair_similarity + krul_select_pairs" if args.two_calls else "krul_pair_similarity_select",
+                   "input_buffer_sets": len(sets)},
+        "roofline": main_roof,
+        "roofline_hbm": hbm, "roofline_mfma": mfma, "roofline_alu": alu,
         "selected_pairs": pairs.cpu().tolist()[0],
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w)
+        res["cpu_baseline"] = cpu_baseline(w, q, k)
     print(json.dumps(res))
 
 

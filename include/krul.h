@@ -43,10 +43,9 @@ enum {
                                           including its own position, j <= n_hist - n_query + t (a decode
                                           step, n_query = 1, or a chunk of a prefill; Sec. 5).  Needs
                                           n_hist >= n_query.  Without it every row sees all n_hist keys. */
-    KRUL_FLAG_GENERIC_KERNEL = 1 << 8, /* testing aid: use the portable VALU kernel even where the
-                                          MFMA kernel applies (results agree to rounding) */
-    KRUL_FLAG_SINGLE_SPLIT = 1 << 9    /* do not split a row's keys over several workgroups
-                                          (less parallelism; exercises the multi-tile path) */
+    /* test aids (see "Measurement and test aids" at the end of this file) */
+    KRUL_FLAG_GENERIC_KERNEL = 1 << 8,
+    KRUL_FLAG_SINGLE_SPLIT = 1 << 9
 };
 
 /*
@@ -238,23 +237,12 @@ int krul_all_pairs_similarity_in_place(const krul_shape_t *shape, const void *q,
                                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * krul_pair_similarity with two caller-created HIP events (hipEvent_t passed as void*,
- * either may be NULL) recorded on the stream immediately before and after the
- * similarity kernel -- the kernel that forms the logits and the softmax sums and
- * dominates the run time -- so that a harness can time that one kernel inside its own
- * timed region.  Everything else is as for krul_pair_similarity.
- */
-int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const void *k,
-                               float *pair_score, float *head_score, float *pair_dist,
-                               void *workspace, size_t workspace_bytes, void *stream,
-                               void *event_begin, void *event_end);
-
-/*
  * Greedy disjoint pair selection (Alg. 1 second loop; Sec. 4.2).  Candidates are
  * the adjacent pairs l -> (l, l+1) whose two layers are both eligible.  They are
  * ordered by pair_score descending (= distance ascending), equal scores by lower l
  * first, and scanned once: a pair is taken iff neither of its layers is already in
- * a taken pair; the scan stops at n_select pairs.
+ * a taken pair; the scan stops at n_select pairs.  A pair whose score is NaN is no candidate
+ * (it is never taken and blocks no neighbour); +-infinity order as numbers.
  *
  *   pair_score [B][n_layers-1] float   device
  *   eligible   [B][n_layers] uint8     device, or NULL = every layer eligible
@@ -277,7 +265,9 @@ int krul_select_pairs(const float *pair_score, const uint8_t *eligible,
  *
  *   eligible, n_select, out_pairs, out_count   as for krul_select_pairs (eligible is an input here: take it
  *                                              from an earlier krul_pair_similarity_ir, or pass NULL)
- *   event_begin, event_end                     as for krul_pair_similarity_timed, either may be NULL
+ *   event_begin, event_end                     caller-created HIP events (hipEvent_t as void*), either may be NULL,
+ *                                              recorded on the stream just before and just after the
+ *                                              similarity kernel (see krul_pair_similarity_timed)
  *   everything else                            as for krul_pair_similarity
  */
 int krul_pair_similarity_select(const krul_shape_t *shape, const void *q, const void *k,
@@ -288,8 +278,9 @@ int krul_pair_similarity_select(const krul_shape_t *shape, const void *q, const 
                                 void *event_begin, void *event_end);
 
 /*
- * Similarity of EVERY two layers i > j, as Alg. 1 is printed ("for every two weights A_i, A_j (i > j)",
- * Sec. 4.2; the layer-by-layer similarity map of Sec. 2.3), not only of neighbours.  Same definitions as
+ * Similarity of EVERY two layers i > j, as Alg. 1 is printed (its second loop runs over all two-layer
+ * combinations of the remaining layers, Sec. 4.2; the layer-by-layer similarity map of Sec. 2.3), not only of
+ * neighbours.  Same definitions as
  * krul_pair_similarity: per conversation, query head and query row the cosine and the Euclidean distance
  * between the attention rows that layers i and j give the row; mean over rows (Sec. 5, Sec. 7), then the
  * average over heads (Sec. 4.2).
@@ -320,7 +311,7 @@ int krul_all_pairs_similarity(const krul_shape_t *shape, const void *q, const vo
  * entries below the diagonal are read).  closer_is_smaller != 0: the score is a distance, taken in
  * ascending order (Alg. 1's Euclidean distance); 0: a similarity, taken in descending order.  Equal
  * scores: lower j first, then lower i.  A pair is taken iff neither of its layers is in a taken pair;
- * the scan stops at n_select pairs.
+ * the scan stops at n_select pairs.  A pair whose score is NaN is no candidate.
  *
  *   score      [B][n_layers][n_layers] float   device (e.g. pair_dist_all or pair_score_all)
  *   eligible   [B][n_layers] uint8             device, or NULL = every layer eligible
@@ -340,6 +331,32 @@ int krul_select_pairs_all(const float *score, int32_t closer_is_smaller, const u
  */
 int32_t krul_n_select_from_ratio(int32_t n_layers, float r_l);
 
+/* Static description of a status code.  Host-only. */
+const char *krul_strerror(int status);
+
+/* ------------------------------------------------------------------------------------------------
+ * Measurement and test aids.  Not part of the method: a benchmark harness and the parity tests use
+ * them; a serving stack has no need to.
+ * ------------------------------------------------------------------------------------------------
+ *
+ * KRUL_FLAG_GENERIC_KERNEL (flags of krul_shape_t): use the portable vector-ALU kernel even where the
+ *     matrix-core kernel applies (results agree to rounding).
+ * KRUL_FLAG_SINGLE_SPLIT: do not split a row's keys over several workgroups (less parallelism; drives
+ *     the path that carries running sums from one key tile to the next).
+ */
+
+/*
+ * krul_pair_similarity with two caller-created HIP events (hipEvent_t passed as void*,
+ * either may be NULL) recorded on the stream immediately before and after the
+ * similarity kernel -- the kernel that forms the logits and the softmax sums and
+ * dominates the run time -- so that a harness can time that one kernel inside its own
+ * timed region.  Everything else is as for krul_pair_similarity.
+ */
+int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const void *k,
+                               float *pair_score, float *head_score, float *pair_dist,
+                               void *workspace, size_t workspace_bytes, void *stream,
+                               void *event_begin, void *event_end);
+
 /*
  * Measurement aid: a plain device-to-device copy kernel (src -> dst, both device, 16-byte
  * aligned, bytes a multiple of 16) on the caller's stream.  It reads `bytes` and writes
@@ -348,8 +365,6 @@ int32_t krul_n_select_from_ratio(int32_t n_layers, float r_l);
  */
 int krul_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
 
-/* Static description of a status code.  Host-only. */
-const char *krul_strerror(int status);
 
 #ifdef __cplusplus
 }

@@ -243,6 +243,8 @@ int krul_oracle_pair_similarity(const oracle_shape_t *s, const void *q, const vo
  * (eligible == NULL: all are).  Candidates are stably ordered by score (equal
  * scores: lower layer index first) and scanned once; a pair is taken iff neither
  * of its layers has been taken; the scan stops once n_select pairs are held.
+ * A pair whose score is NaN has no place in the order and is never a candidate
+ * (the paper is silent on non-finite scores).
  * out_pairs[b][n_select] gets the lower layer index of each chosen pair in the
  * order chosen, -1 beyond out_count[b].
  */
@@ -261,7 +263,7 @@ int krul_oracle_select_pairs(const double *pair_score, const uint8_t *eligible,
         const uint8_t *el = eligible ? eligible + (size_t)b * n_layers : NULL;
         int n = 0;
         for (int l = 0; l < NP; ++l)
-            if (!el || (el[l] && el[l + 1]))
+            if ((!el || (el[l] && el[l + 1])) && sc[l] == sc[l])   /* a pair whose score is NaN is no candidate */
                 order[n++] = l;
         /* stable insertion sort, descending score */
         for (int i = 1; i < n; ++i) {
@@ -336,9 +338,9 @@ int krul_oracle_ir_mass(const oracle_shape_t *s, const void *q, const void *k,
 }
 
 /*
- * Alg. 1 as printed scores EVERY two layers i > j, not only neighbours ("for every two weights
- * A_i, A_j (i > j)", Sec. 4.2; the similarity figure of Sec. 2.3 shows the full layer-by-layer
- * map).  For every conversation b, query head h and layers i != j: the mean over the query rows
+ * Alg. 1 as printed scores EVERY two layers i > j, not only neighbours (its second loop runs
+ * over all two-layer combinations of the remaining layers, Sec. 4.2; the similarity figure of
+ * Sec. 2.3 shows the full layer-by-layer map).  For every conversation b, query head h and layers i != j: the mean over the query rows
  * of the cosine similarity and of the Euclidean distance between the rows that layers i and j
  * give the same token; then the average over heads.
  *   head_cos / head_dist : [B][Hq][L][L]   (may be NULL)
@@ -456,7 +458,7 @@ int krul_oracle_select_pairs_all(const double *score, int closer_is_smaller, con
         int n = 0;
         for (int j = 0; j < L; ++j)
             for (int i = j + 1; i < L; ++i)
-                if (!el || (el[i] && el[j])) {
+                if ((!el || (el[i] && el[j])) && sc[(size_t)i * L + j] == sc[(size_t)i * L + j]) {   /* (NaN: no candidate) */
                     cj[n] = j;
                     ci[n] = i;
                     /* one ordering for both readings: ascending key */

@@ -748,6 +748,7 @@ __global__ __launch_bounds__(kSelThreads) void select_all_kernel(
                 const int i = e / L, j = e % L;
                 if (i <= j || is_used(i) || is_used(j)) continue;
                 const float key = keys[e];
+                if (key != key) continue;   // a NaN score: no candidate
                 const int rk = j * L + i;
                 if (rank == INT32_MAX || key < best || (key == best && rk < rank)) {
                     best = key;
@@ -797,6 +798,7 @@ __global__ __launch_bounds__(kSelThreads) void select_all_kernel(
             const int i = e / L, j = e % L;
             if (i <= j || used[i] || used[j]) continue;
             const float key = in_lds ? keys[e] : (closer_is_smaller ? sc[e] : -sc[e]);
+            if (key != key) continue;   // a NaN score: no candidate
             const int rk = j * L + i;
             if (rank == INT32_MAX || key < best || (key == best && rk < rank)) {
                 best = key;

@@ -1,12 +1,13 @@
 // Greedy disjoint choice among adjacent layer pairs (Alg. 1, second loop; Sec. 4.2) for one
 // conversation, run by all threads of a workgroup: shared by the selection kernel and by the
-// similarity pass that selects in its last workgroup.
+// kernel that averages heads and selects in one launch.
 //
 // The candidates (adjacent pairs whose two layers are eligible) are ranked by counting:
 // rank(l) = number of candidates that come before l in the order "higher score first, equal
 // scores lower index first".  That is the stable descending sort the algorithm asks for, with no
 // data-dependent control flow.  One thread then scans the ranked list and takes a pair iff both
-// its layers are still free, until n_select pairs are held.
+// its layers are still free, until n_select pairs are held.  A pair whose score is NaN has no
+// place in that order: it is no candidate (so the order stays total and the ranks dense).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -39,14 +40,14 @@ __device__ inline void select_adjacent(const float *score, const uint8_t *el, in
     __syncthreads();
 
     for (int l = threadIdx.x; l < NP; l += nt) {
-        if (!cand[l]) continue;
         const float s = score[l];
+        if (!cand[l] || s != s) continue;
         int rank = 0;
 #pragma unroll 8
         for (int j = 0; j < NP; ++j) {
             const float sj = score[j];
             // j precedes l unless l's score is strictly higher, or equal with l first
-            rank += (cand[j] && (sj > s || (!(sj < s) && j < l))) ? 1 : 0;
+            rank += (cand[j] && sj == sj && (sj > s || (!(sj < s) && j < l))) ? 1 : 0;
         }
         order[rank] = l;
     }

@@ -110,6 +110,8 @@ def test_select_all_is_bit_exact(G, oracle):
             sc = (rng.integers(0, 5, size=(B, L, L)) / 4.0).astype(np.float32)    # many exact ties
         else:
             sc = rng.random((B, L, L)).astype(np.float32)
+        if trial % 5 == 1:
+            sc[rng.random((B, L, L)) < 0.2] = np.nan                              # NaN: no candidate, on both sides
         el = (rng.random((B, L)) > 0.2).astype(np.uint8)
         n_select = int(rng.integers(0, L // 2 + 1))
         for smaller in (True, False):

@@ -3,8 +3,10 @@ bench.py times.  C2 is compared whole (every head score, every pair score, the
 selection).  C3 and C4 are too large for the fp64 oracle to run whole in seconds, so a
 seeded sample of (conversation, pair, head) units is computed by the oracle -- all query
 rows and all keys of each sampled unit -- and compared element by element; range and
-selector properties are checked on the full output.  C5 (22.5 GiB of inputs) is run with
-the same layer/head structure and a reduced batch, history and query count."""
+selector properties are checked on the full output.  C5 (22.5 GiB of inputs) is drawn on the
+device (the same recipe, torch's seeded generator) and run at its own size: sampled units
+spread over all eight conversations are copied back for the oracle; a reduced copy of its
+layer/head structure is kept as a quick case."""
 import numpy as np
 import pytest
 import torch
@@ -88,3 +90,71 @@ def test_c5_shape_reduced(G, oracle):
     assert (w.L, w.Hq, w.Hkv) == (80, 64, 8)
     got = sampled_check(G, oracle, w, 48, 5)
     assert got["pair_score"].shape == (2, 79)
+
+
+def test_c5_full(G, oracle):
+    """C5 at its own size (8 conversations, 80 layers, 64/8 heads, 16384 x 256 tokens), in the launch
+    configuration bench.py times: 24 sampled (conversation, pair, head) units, three per conversation, against
+    the oracle on the same bits; ranges on the whole output; the device selector against the oracle selector
+    on all 8 x 20 choices."""
+    import paper_2507_08045_amd as kr
+    free, _total = torch.cuda.mem_get_info()
+    if free < 40 * 2**30:
+        pytest.skip("needs about 30 GiB of device memory")
+    print("[C5 full] drawing 22.5 GiB of inputs on the device", flush=True)
+    q, k, info = workloads.config_device("C5")
+    torch.cuda.synchronize()
+    B, L, Hq, n_select = info["B"], info["L"], info["Hq"], info["n_select"]
+    assert (B, L, Hq, info["Hkv"], info["S"], info["Tq"], n_select) == (8, 80, 64, 8, 16384, 256, 20)
+    print("[C5 full] scoring", flush=True)
+    shp = kr.make_shape(q, k)
+    ws = torch.empty(kr.workspace_bytes(shp), dtype=torch.uint8, device="cuda")
+    # what bench.py times: cosine only, scoring and selection in one call
+    one = kr.pair_similarity_select(q, k, n_select, workspace=ws)
+    torch.cuda.synchronize()
+    hs = one["head_score"].cpu().numpy()
+    ps = one["pair_score"].cpu().numpy()
+    assert hs.shape == (B, L - 1, Hq) and ps.shape == (B, L - 1)
+    assert np.all(np.isfinite(hs)) and np.all(hs > 0) and np.all(hs <= 1 + 1e-5)
+    np.testing.assert_allclose(ps, hs.mean(axis=2), atol=1e-6)   # head average
+    rng = np.random.default_rng(55)
+    units = [(b, int(rng.integers(0, L - 1)), int(rng.integers(0, Hq))) for b in range(B) for _ in range(3)]
+    units[0] = (0, 0, 0)
+    units[-1] = (B - 1, L - 2, Hq - 1)
+    qs, ks = workloads.units_to_host(q, k, units)
+    print(f"[C5 full] oracle on {len(units)} units", flush=True)
+    want = oracle.pair_similarity(qs, ks)
+    hc, hd = want["head_score"][:, 0, 0], want["head_dist"][:, 0, 0]
+    err = float(np.max(np.abs(np.array([hs[u] for u in units]) - hc)))
+    print(f"[C5 full] {len(units)} sampled units: max |gpu - oracle| = {err:.2e}", flush=True)
+    assert err <= G.TOL
+    # selection: device selector == oracle selector on the same fp32 scores, every conversation
+    wp, wc = oracle.select_pairs(ps.astype(np.float64), n_select)
+    np.testing.assert_array_equal(one["pairs"].cpu().numpy(), wp)
+    np.testing.assert_array_equal(one["count"].cpu().numpy(), wc)
+    assert np.all(wc == n_select)
+    for b in range(B):   # disjoint layers, best pair first
+        used = set()
+        for l in wp[b]:
+            assert l not in used and l + 1 not in used
+            used.update((int(l), int(l) + 1))
+        assert wp[b, 0] == int(np.argmax(ps[b]))
+    assert len({tuple(r) for r in wp.tolist()}) > 1   # conversations differ in their correlations, so in their choice
+    # scores follow the generator's correlations
+    assert np.corrcoef(info["rho_k"][:, :, 0].ravel(), ps.ravel())[0, 1] > 0.97
+    # with the distance by-product: the same cosines, distances against the oracle's direct difference
+    del one
+    out = kr.pair_similarity(q, k, workspace=ws)
+    torch.cuda.synchronize()
+    hs2 = out["head_score"].cpu().numpy()
+    assert np.max(np.abs(hs2 - hs)) < 1e-6
+    pd = out["pair_dist"].cpu().numpy()
+    assert np.all(pd >= 0) and np.all(pd <= np.sqrt(2) + 1e-5)
+    # pair_dist averages a pair's heads: compare it, the pair score and all 64 head scores for one whole pair
+    b0, l0 = 3, 41
+    full_pair = [(b0, l0, h) for h in range(Hq)]
+    qs2, ks2 = workloads.units_to_host(q, k, full_pair)
+    w2 = oracle.pair_similarity(qs2, ks2)
+    assert abs(pd[b0, l0] - float(np.mean(w2["head_dist"][:, 0, 0]))) <= G.TOL
+    assert abs(ps[b0, l0] - float(np.mean(w2["head_score"][:, 0, 0]))) <= G.TOL
+    G.assert_close(hs[b0, l0], w2["head_score"][:, 0, 0], G.TOL, "C5 head scores of one whole pair")

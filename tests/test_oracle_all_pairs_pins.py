@@ -122,26 +122,22 @@ def test_neighbours_agree_with_the_adjacent_reading_and_closed_forms(oracle):
 
 # ---------------------------------------------------------------- selection over every two layers
 
-def alg1_literal_all(D, eligible, n_layers, r_l):
-    """Alg. 1 as stated, with sets and the built-in stable sort: D[i][j] for i > j among eligible
-    layers, ascending; take (i, j) iff neither is shared; stop when |S| >= N * r_l."""
-    cand = []
-    for j in range(n_layers):
-        for i in range(j + 1, n_layers):
-            if eligible[i] and eligible[j]:
-                cand.append((D[i][j], j, i))
-    cand = sorted(cand, key=lambda e: e[0])
-    S, M = set(), []
-    if n_layers * r_l <= 0:
-        return M
-    for _, j, i in cand:
-        if i in S or j in S:
-            continue
-        S |= {i, j}
-        M.append((j, i))
-        if len(S) >= n_layers * r_l:
+def best_free_two_layers_repeatedly(D, eligible, n_layers, r_l):
+    """The greedy rule with no sorting: again and again take the closest two layers that are both still free and
+    eligible (D[i][j], i > j; equal values: the lower j, then the lower i), until n_layers * r_l layers are
+    shared or none is left.  Pairs as (j, i) in the order taken."""
+    free = [bool(e) for e in eligible]
+    taken = []
+    while 2 * len(taken) < n_layers * r_l:
+        open_pairs = [(j, i) for j in range(n_layers) for i in range(j + 1, n_layers)
+                      if free[i] and free[j] and not math.isnan(D[i][j])]
+        if not open_pairs:
             break
-    return M
+        closest = min(D[i][j] for j, i in open_pairs)
+        j, i = min((j, i) for j, i in open_pairs if D[i][j] == closest)
+        free[i] = free[j] = False
+        taken.append((j, i))
+    return taken
 
 
 def test_selection_exhaustive_orderings_small(oracle):
@@ -155,7 +151,7 @@ def test_selection_exhaustive_orderings_small(oracle):
                 D[j, i] = -7.0           # the upper triangle must not be read
             for n_select in range(0, L // 2 + 1):
                 pairs, count = oracle.select_pairs_all(D, n_select, closer_is_smaller=True)
-                want = alg1_literal_all(D, [1] * L, L, 2 * n_select / L)
+                want = best_free_two_layers_repeatedly(D, [1] * L, L, 2 * n_select / L)
                 assert [tuple(p) for p in pairs[0, :count[0]]] == want, (L, perm, n_select)
                 assert np.all(pairs[0, count[0]:] == -1)
                 # a similarity is the same choice on the negated matrix
@@ -171,8 +167,22 @@ def test_selection_random_masks_and_ties(oracle):
         el = (rng.random(L) > 0.25).astype(np.uint8)
         n_select = int(rng.integers(0, L // 2 + 1))
         pairs, count = oracle.select_pairs_all(D, n_select, closer_is_smaller=True, eligible=el)
-        want = alg1_literal_all(D, el, L, 2 * n_select / L)
+        want = best_free_two_layers_repeatedly(D, el, L, 2 * n_select / L)
         assert [tuple(p) for p in pairs[0, :count[0]]] == want, (D, el, n_select)
+
+
+def test_selection_nan_is_no_candidate(oracle):
+    rng = np.random.default_rng(37)
+    for _ in range(200):
+        L = int(rng.integers(2, 9))
+        D = rng.integers(0, 4, size=(L, L)) / 4.0
+        D[rng.random((L, L)) < 0.3] = float("nan")
+        el = (rng.random(L) > 0.2).astype(np.uint8)
+        n_select = int(rng.integers(0, L // 2 + 1))
+        for smaller in (True, False):
+            pairs, count = oracle.select_pairs_all(D, n_select, closer_is_smaller=smaller, eligible=el)
+            want = best_free_two_layers_repeatedly(D if smaller else -D, el, L, 2 * n_select / L)
+            assert [tuple(p) for p in pairs[0, :count[0]]] == want, (D, el, n_select)
 
 
 def test_selection_properties_large(oracle):

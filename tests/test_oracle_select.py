@@ -1,8 +1,10 @@
 """Pins for the oracle's pair selector (Alg. 1, second loop; Sec. 4.2) -- CPU only.
 
-The reference here is a literal Python transcription of the algorithm's steps with
-sets and the built-in sort, run over every ordering of the scores for small layer
-counts, plus the properties the greedy rule implies.
+The reference here states the greedy rule without any sorting: again and again take the
+best pair that is still free (both layers unused and eligible; equal scores: the lower
+layer), until the budget of shared layers is met or no pair is left.  A sorted list walked
+once picks exactly these pairs, in this order.  It is run over every ordering of the scores
+for small layer counts, beside the properties the rule implies.
 """
 import itertools
 import math
@@ -13,28 +15,20 @@ import numpy as np
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def alg1_literal(scores, eligible, n_layers, r_l):
-    """Alg. 1 as stated: distances ascending, take (i,j) iff i,j not in S, stop when
-    |S| >= N * r_l.  Distance = -score; candidates are the adjacent pairs of
-    eligible layers."""
-    D = []
-    for j in range(n_layers - 1):
-        i = j + 1
-        if eligible[i] and eligible[j]:
-            D.append((-scores[j], j, i))
-    D = sorted(D, key=lambda e: e[0])          # stable: ties keep ascending j
-    S, M = set(), []
-    if n_layers * r_l <= 0:
-        return M
-    for _, j, i in D:
-        if i not in S and j not in S:
-            S |= {i, j}
-            M.append(j)
-        else:
-            continue
-        if len(S) >= n_layers * r_l:
+def best_free_pair_repeatedly(scores, eligible, n_layers, r_l):
+    """Pairs (lower layer index) in the order taken; the budget is n_layers * r_l shared layers."""
+    free = [bool(e) for e in eligible]
+    taken = []
+    while 2 * len(taken) < n_layers * r_l:
+        open_pairs = [l for l in range(n_layers - 1)
+                      if free[l] and free[l + 1] and not math.isnan(scores[l])]
+        if not open_pairs:
             break
-    return M
+        top = max(scores[l] for l in open_pairs)
+        l = min(l for l in open_pairs if scores[l] == top)
+        free[l] = free[l + 1] = False
+        taken.append(l)
+    return taken
 
 
 def test_exhaustive_orderings_small(oracle):
@@ -45,7 +39,7 @@ def test_exhaustive_orderings_small(oracle):
             for r_l in (0.25, 0.5, 1.0):
                 n_select = math.ceil(L * r_l / 2)
                 pairs, count = oracle.select_pairs(scores, n_select)
-                want = alg1_literal(scores, [1] * L, L, r_l)
+                want = best_free_pair_repeatedly(scores, [1] * L, L, r_l)
                 assert list(pairs[0, :count[0]]) == want, (L, perm, r_l)
                 assert all(p == -1 for p in pairs[0, count[0]:])
 
@@ -58,7 +52,7 @@ def test_exhaustive_masks_and_ties(oracle):
             scores = rng.integers(0, 3, size=L - 1) / 4.0        # many exact ties
             for n_select in (1, 2, 3):
                 pairs, count = oracle.select_pairs(scores, n_select, eligible=np.array(mask))
-                want = alg1_literal(scores, mask, L, 2 * n_select / L)
+                want = best_free_pair_repeatedly(scores, mask, L, 2 * n_select / L)
                 assert list(pairs[0, :count[0]]) == want, (mask, scores, n_select)
 
 
@@ -116,3 +110,23 @@ def test_six_layer_golden(oracle):
     pairs, count = oracle.select_pairs(scores, int(vals["n_select"][0]))
     assert list(pairs[0]) == [int(x) for x in vals["pairs"]]
     assert sorted(l for p in pairs[0] for l in (p, p + 1)) == list(range(6))
+
+
+def test_nan_scores_are_no_candidates(oracle):
+    # the paper is silent on non-finite scores: a pair whose score is NaN is never taken and blocks nothing
+    nan = float("nan")
+    pairs, count = oracle.select_pairs([0.8, nan, 0.7, nan, 0.2], 3)
+    assert list(pairs[0]) == [0, 2, 4] and count[0] == 3
+    pairs, count = oracle.select_pairs([nan, nan, nan], 2)
+    assert list(pairs[0]) == [-1, -1] and count[0] == 0
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        L = int(rng.integers(2, 12))
+        scores = rng.integers(0, 4, size=L - 1) / 4.0
+        scores[rng.random(L - 1) < 0.3] = nan
+        el = (rng.random(L) > 0.2).astype(np.uint8)
+        n_select = int(rng.integers(0, L // 2 + 1))
+        pairs, count = oracle.select_pairs(scores, n_select, eligible=el)
+        want = best_free_pair_repeatedly(scores, el, L, 2 * n_select / L)
+        assert list(pairs[0, :count[0]]) == want
+        assert all(p == -1 for p in pairs[0, count[0]:])

@@ -155,3 +155,68 @@ def scaled(name: str, *, S=None, Tq=None, L=None, batch=None, seed=None) -> Work
     kw = dict(sink_frac=0.02, sink_gain=4.0) if name == "C3" else {}
     return make(name + "-cut", B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S or S0, Tq=Tq or Tq0, dtype=dtype,
                 n_select=max(1, L // 4), rho_k=rho, seed=seed, **kw)
+
+
+def config_device(name: str, *, device="cuda", batch=None, seed=None):
+    """The same recipe drawn ON THE DEVICE with torch's seeded Philox generator, for configurations whose
+    host draw takes minutes (C5: 22.5 GiB).  Returns (q, k, info): q [B, L, Hq, Tq, d] and k [B, L, Hkv, S, d]
+    as device tensors of the storage type, info = dict(name, shape fields, n_select, rho_k [B, L-1, Hkv] numpy,
+    rho_q, sinks).  The numbers differ from config()'s numpy draw (another generator), the recipe does not."""
+    import torch
+    B, L, Hq, Hkv, d, S, Tq, dtype, n_select = CONFIGS[name]
+    if batch is not None:
+        B = batch
+    seed = BASE_SEED + _CFG_ID[name] if seed is None else seed
+    rr = _rng(seed, 6)
+    if name == "C1":
+        rho = np.full((B, L - 1, Hkv), 0.8)
+    elif name == "C4":
+        rho = rr.uniform(0.5, 0.95, size=(B, L - 1, Hkv))
+    else:
+        rho = np.broadcast_to(rr.uniform(0.5, 0.95, size=(B, L - 1, 1)), (B, L - 1, Hkv)).copy()
+    rho = rho.astype(np.float32)
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[dtype]
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    q = torch.empty((B, L, Hq, Tq, d), dtype=tdt, device=device)
+    k = torch.empty((B, L, Hkv, S, d), dtype=tdt, device=device)
+    sinks = np.zeros(0, dtype=np.int64)
+    gain = None
+    if name in ("C3", "D2"):
+        n_sink = max(1, int(round(0.02 * S)))
+        sinks = np.sort(_rng(seed, 5).choice(S, size=n_sink, replace=False))
+        gain = torch.ones((1, S, 1), dtype=torch.float32, device=device)
+        gain[0, torch.from_numpy(sinks).to(device), 0] = 4.0
+    rho_q = 0.95
+    cq = float(np.sqrt(1.0 - rho_q * rho_q))
+    rho_t = torch.from_numpy(rho).to(device)
+    for b in range(B):
+        qc = torch.randn((Hq, Tq, d), generator=g, device=device, dtype=torch.float32)
+        kc = torch.randn((Hkv, S, d), generator=g, device=device, dtype=torch.float32)
+        for l in range(L):
+            if l > 0:
+                r = rho_t[b, l - 1][:, None, None]
+                kc = r * kc + torch.sqrt(1.0 - r * r) * torch.randn((Hkv, S, d), generator=g, device=device,
+                                                                    dtype=torch.float32)
+                qc = rho_q * qc + cq * torch.randn((Hq, Tq, d), generator=g, device=device, dtype=torch.float32)
+            q[b, l] = qc.to(tdt)
+            k[b, l] = (kc if gain is None else kc * gain).to(tdt)
+    info = dict(name=name, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, dtype=dtype, n_select=n_select,
+                rho_k=rho, rho_q=rho_q, sinks=sinks, score_elems=B * (L - 1) * Hq * Tq * S)
+    return q, k, info
+
+
+def units_to_host(q, k, units):
+    """Copy the inputs of chosen (b, l, h) units -- query head h and its kv head, layers l and l+1 -- from device
+    tensors to the host, as one small problem per unit: (q_units [n, 2, 1, Tq, d], k_units [n, 2, 1, S, d]),
+    numpy arrays of the storage type's bits (bf16 as uint16).  Unit i is conversation i of that problem, with two
+    layers and one head, so its one head score is the score of (b, l, h)."""
+    import torch
+    g = q.shape[2] // k.shape[2]
+    qs = torch.stack([q[b, l:l + 2, h] for b, l, h in units])[:, :, None]
+    ks = torch.stack([k[b, l:l + 2, h // g] for b, l, h in units])[:, :, None]
+
+    def bits(t):
+        t = t.contiguous().cpu()
+        return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+    return bits(qs), bits(ks)
