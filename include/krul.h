@@ -9,7 +9,8 @@
  * Conventions for every entry point
  *   - All tensor arguments are DEVICE pointers unless stated; the caller owns every
  *     buffer.  The library allocates no device memory, keeps no state between
- *     calls and is re-entrant.
+ *     calls and is re-entrant (krul_pair_similarity_static alone works in a scratch
+ *     area of the library's own; see there).
  *   - Work is only enqueued on the caller's stream (hipStream_t passed as void*,
  *     NULL = the default stream); calls return without synchronising.
  *   - The return value is a krul_status_t.  Nothing throws or aborts across the ABI.
@@ -31,7 +32,8 @@ typedef enum {
     KRUL_EDTYPE = -2,       /* dtype is not a krul_dtype_t */
     KRUL_EWORKSPACE = -3,   /* workspace missing, misaligned or shorter than the query says */
     KRUL_ELAUNCH = -4,      /* the HIP runtime refused a launch */
-    KRUL_EUNSUPPORTED = -5  /* valid request with no kernel (head_dim, n_layers limits) */
+    KRUL_EUNSUPPORTED = -5, /* valid request with no kernel (head_dim, n_layers limits) */
+    KRUL_ESCRATCH = -6      /* krul_pair_similarity_static: the shape needs more than KRUL_STATIC_SCRATCH_BYTES */
 } krul_status_t;
 
 typedef enum { KRUL_F32 = 0, KRUL_BF16 = 1, KRUL_F16 = 2 /* IEEE binary16 */ } krul_dtype_t;
@@ -101,6 +103,28 @@ size_t krul_pair_similarity_workspace(const krul_shape_t *shape);
 int krul_pair_similarity(const krul_shape_t *shape, const void *q, const void *k,
                          float *pair_score, float *head_score, float *pair_dist,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * krul_pair_similarity for callers that cannot provide a workspace because they cannot allocate device
+ * memory where they stand: code recorded into a HIP graph, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without the workspace, same results bit for bit.  The scratch memory is a
+ * fixed area of KRUL_STATIC_SCRATCH_BYTES that the library's code object holds on every GPU it is loaded
+ * on until the process ends; the call allocates nothing and frees nothing.
+ *
+ *   - Shapes whose krul_pair_similarity_workspace() exceeds KRUL_STATIC_SCRATCH_BYTES are refused with
+ *     KRUL_ESCRATCH (nothing enqueued).  40 MiB holds every few-query and decode-step shape of the
+ *     Llama-3-8B kind (64 query tokens over 4096 keys: 16 MiB; one token over 131072 keys: 32 MiB); the
+ *     many-query shapes need hundreds of MiB and take krul_pair_similarity with a workspace.
+ *   - The stream must belong to the CURRENT device.  The first call on a device looks up the area's
+ *     address there (no allocation); make that first call outside graph capture.
+ *   - All calls on one GPU share the one area: calls that overlap in time on one GPU (two streams, two
+ *     threads) race.  Calls on one stream are ordered and safe.  Nothing in the area needs clearing
+ *     between calls: every record read is written first by the same call.
+ * Errors otherwise as for krul_pair_similarity.
+ */
+#define KRUL_STATIC_SCRATCH_BYTES (40u << 20)
+int krul_pair_similarity_static(const krul_shape_t *shape, const void *q, const void *k,
+                                float *pair_score, float *head_score, float *pair_dist, void *stream);
 
 /*
  * krul_pair_similarity together with the Initial-Recent (I-R) layer test that precedes it in

@@ -18,6 +18,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libkrul.so")
 
 KRUL_OK, KRUL_EINVAL, KRUL_EDTYPE, KRUL_EWORKSPACE, KRUL_ELAUNCH, KRUL_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+KRUL_ESCRATCH = -6
+KRUL_STATIC_SCRATCH_BYTES = 40 << 20
 KRUL_F32, KRUL_BF16, KRUL_F16 = 0, 1, 2
 _DTYPES = {torch.float32: KRUL_F32, torch.bfloat16: KRUL_BF16, torch.float16: KRUL_F16}
 KRUL_FLAG_CAUSAL = 1 << 0
@@ -72,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.krul_pair_similarity_workspace.argtypes = [ctypes.POINTER(KrulShape)]
         L.krul_pair_similarity.restype = ctypes.c_int
         L.krul_pair_similarity.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.krul_pair_similarity_static.restype = ctypes.c_int
+        L.krul_pair_similarity_static.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp]
         L.krul_pair_similarity_timed.restype = ctypes.c_int
         L.krul_pair_similarity_timed.argtypes = [ctypes.POINTER(KrulShape), vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
         L.krul_pair_similarity_ir_workspace.restype = sz
@@ -198,6 +202,23 @@ def pair_similarity(q: torch.Tensor, k: torch.Tensor, *, scale: float = 0.0, fla
     if rc != KRUL_OK:
         raise KrulError(rc)
     return {"pair_score": ps, "head_score": hs, "pair_dist": pd, "workspace": workspace}
+
+
+def pair_similarity_static(q: torch.Tensor, k: torch.Tensor, out: dict, *, scale: float = 0.0, flags: int = 0) -> dict:
+    """krul_pair_similarity_static on the current stream: the scores of pair_similarity with no workspace
+    and no allocation anywhere -- the caller passes every output in `out` ("pair_score" required,
+    "head_score" and "pair_dist" optional) and gets `out` back."""
+    if not (q.is_cuda and k.is_cuda):
+        raise ValueError("q and k must be GPU tensors (this library has no CPU path)")
+    if not (q.is_contiguous() and k.is_contiguous()):
+        raise ValueError("q and k must be contiguous")
+    shp = make_shape(q, k, scale, flags)
+    rc = lib().krul_pair_similarity_static(ctypes.byref(shp), _dev_ptr(q), _dev_ptr(k), _dev_ptr(out["pair_score"]),
+                                           _dev_ptr(out.get("head_score")), _dev_ptr(out.get("pair_dist")),
+                                           ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
+    return out
 
 
 class StridedKeys:

@@ -2,6 +2,8 @@
 // the contract of each entry point.
 #include <math.h>
 
+#include <mutex>
+
 #include "krul_common.h"
 
 namespace krul {
@@ -339,6 +341,50 @@ int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const v
                           workspace, workspace_bytes, stream, event_begin, event_end);
 }
 
+}  // extern "C"
+
+namespace {
+// The scratch area of krul_pair_similarity_static: device memory the code object brings along, one copy
+// per GPU.  In host code the array's name only stands for the symbol; its device address is asked for
+// once per GPU (that GPU current) and kept.
+static __device__ __align__(256) unsigned char scratch[KRUL_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices];   // by device ordinal; null until the first call on that device
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KRUL_ELAUNCH;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return KRUL_ELAUNCH;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return KRUL_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int krul_pair_similarity_static(const krul_shape_t *shape, const void *q, const void *k,
+                                float *pair_score, float *head_score, float *pair_dist, void *stream)
+{
+    Plan pl;
+    const int rc = make_plan(shape, &pl);
+    if (rc != KRUL_OK) return rc;
+    if (pl.total_bytes > (size_t)KRUL_STATIC_SCRATCH_BYTES) return KRUL_ESCRATCH;
+    void *ptr = nullptr;
+    const int src = static_scratch(&ptr);
+    if (src != KRUL_OK) return src;
+    // Nothing in the area has to start at zero: every record the finalize kernels read is written by the
+    // similarity kernel of the same call first.
+    return run_similarity(shape, q, k, pair_score, head_score, pair_dist, false, 0.f, nullptr, nullptr,
+                          ptr, (size_t)KRUL_STATIC_SCRATCH_BYTES, stream, nullptr, nullptr);
+}
+
 int krul_pair_similarity_strided(const krul_shape_t *shape, const void *q, const krul_k_layout_t *k_layout,
                                  float *pair_score, float *head_score, float *pair_dist,
                                  void *workspace, size_t workspace_bytes, void *stream)
@@ -506,6 +552,7 @@ const char *krul_strerror(int status)
     case KRUL_EWORKSPACE: return "workspace missing, misaligned or too small";
     case KRUL_ELAUNCH: return "kernel launch failed";
     case KRUL_EUNSUPPORTED: return "no kernel for this shape";
+    case KRUL_ESCRATCH: return "the problem needs more scratch memory than the library's built-in area holds";
     default: return "unknown status";
     }
 }
