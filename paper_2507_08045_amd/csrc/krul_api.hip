@@ -51,7 +51,7 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
     // zero-padded to the next of the two inside LDS)
     const bool mfma = (s->dtype == KRUL_BF16 || s->dtype == KRUL_F16) && s->head_dim <= 128 &&
                       !(s->flags & KRUL_FLAG_GENERIC_KERNEL);
-    long long n_wg, records, spill_records = 0;
+    long long n_wg, records;
     if (mfma) {
         int kt;
         // Which shape of workgroup tile (rows x keys).  A shape's ordinary form is for problems that give
@@ -88,6 +88,10 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
         // step over 131072 tokens: 57 % of 8 TB/s against 74 % with one tile per split), and the
         // partial records stay below 1 % of the key bytes.  So: one tile per split, up to 1024 splits.
         if (y.variant != kMfmaWide && y.variant != kMfmaWideShort && want < 1024) want = 1024;
+        // The wide tile on a large problem: four key splits (or more) per row tile, so that the workgroups
+        // running side by side on an XCD form patches of 8 row tiles x 4 key splits (patch_rows()) and share
+        // both their query rows and their keys through the L2 -- as long as a split keeps four tiles or more
+        if (y.variant == kMfmaWide && want < 4 && tiles >= 16 && nrt % 8 == 0) want = 4;
         if (want < 1 || (s->flags & KRUL_FLAG_SINGLE_SPLIT)) want = 1;
         long long nsplit = want < tiles ? want : tiles;
         const long long tps = (tiles + nsplit - 1) / nsplit;
@@ -98,7 +102,6 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
         pl->keys_per_split = (int)(tps * kt);
         n_wg = units * nsplit;
         records = n_wg * L * r_wg;
-        if (tps > 1) spill_records = n_wg * L * (y.wr * y.wk) * y.rb * 64;
     } else {
         y.variant = kGeneric;
         y.wr = y.wk = y.rb = 1;
@@ -119,17 +122,14 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
     if (n_wg > INT32_MAX) return KRUL_EUNSUPPORTED;
     pl->n_workgroups = (int)n_wg;
     pl->state_bytes = round_up((size_t)records * sizeof(float4), kAlign);
-    pl->spill_bytes = round_up((size_t)spill_records * sizeof(float4), kAlign);
     const size_t head_bytes = round_up((size_t)(B * (L - 1) * Hq) * sizeof(float), kAlign);
-    pl->spill_off = pl->state_bytes;
-    pl->head_cos_off = pl->spill_off + pl->spill_bytes;
+    pl->head_cos_off = pl->state_bytes;
     pl->head_dist_off = pl->head_cos_off + head_bytes;
     pl->total_bytes = pl->head_dist_off + head_bytes;
-    pl->state_ir_off = pl->spill_ir_off = pl->head_ir_off = 0;
+    pl->state_ir_off = pl->head_ir_off = 0;
     if (want_ir) {
         pl->state_ir_off = pl->total_bytes;
-        pl->spill_ir_off = pl->state_ir_off + round_up((size_t)records * sizeof(float), kAlign);
-        pl->head_ir_off = pl->spill_ir_off + round_up((size_t)spill_records * sizeof(float), kAlign);
+        pl->head_ir_off = pl->state_ir_off + round_up((size_t)records * sizeof(float), kAlign);
         pl->total_bytes = pl->head_ir_off + round_up((size_t)(B * L * Hq) * sizeof(float), kAlign);
     }
     return KRUL_OK;
@@ -233,7 +233,6 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     SimParams p;
     p.q = q;
     p.state = reinterpret_cast<float4 *>(ws);
-    p.spill = reinterpret_cast<float4 *>(ws + pl.spill_off);
     p.B = shape->batch;
     p.L = shape->n_layers;
     p.Hq = shape->n_q_heads;
@@ -252,7 +251,6 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
     p.ir_init_end = (int)floor(0.1 * (double)p.S);
     p.ir_recent_begin = (int)floor(0.9 * (double)p.S);
     p.state_ir = reinterpret_cast<float *>(ws + pl.state_ir_off);
-    p.spill_ir = reinterpret_cast<float *>(ws + pl.spill_ir_off);
     p.lay = pl.lay;
     {
         KeyAddr ka;

@@ -58,10 +58,9 @@ struct Plan {
     int n_workgroups;
     float c;             // scale * log2(e)
     size_t state_bytes;  // merged partial records (float4), read by the finalize kernel
-    size_t spill_bytes;  // per-lane running records of multi-tile splits (MFMA variants)
-    size_t spill_off, head_cos_off, head_dist_off, total_bytes;
-    // Initial-Recent layer test only: one float per record beside state / spill, head means
-    size_t state_ir_off, spill_ir_off, head_ir_off;
+    size_t head_cos_off, head_dist_off, total_bytes;
+    // Initial-Recent layer test only: one float per record beside state, head means
+    size_t state_ir_off, head_ir_off;
 };
 
 // Host: choose kernel and decomposition for a validated shape.  Returns a
@@ -71,14 +70,14 @@ int make_plan(const krul_shape_t *s, Plan *plan, bool want_ir = false);
 struct SimParams {
     const void *q;
     const void *k;
-    float4 *state;   // partial records, indexed by state_index()
-    float4 *spill;   // MFMA variants: per-lane running records between key tiles
+    float4 *state;   // partial records, indexed by state_index() (MFMA variants: also a split's running records
+                     // between its key tiles)
     int B, L, Hq, Hkv, g, d, S, Tq;
     int keys_per_split;
     float c;
     int want_dist;   // the distance is asked for: Z = sum e must be accumulated too
     // Initial-Recent layer test (Sec. 4.2, Alg. 1 first loop): Zir = sum of e over the keys
-    // [0, ir_init_end) and [ir_recent_begin, S), one float per record, laid out like state / spill
+    // [0, ir_init_end) and [ir_recent_begin, S), one float per record, laid out like state
     int want_ir;
     int causal;   // row t sees keys j <= S - Tq + t (KRUL_FLAG_CAUSAL)
     int f16;      // the 16-bit inputs are IEEE binary16, not bfloat16 (MFMA variants)
@@ -94,7 +93,7 @@ struct SimParams {
     int page_shift, max_blocks;
     long long k_stride_page;
     int ir_init_end, ir_recent_begin;
-    float *state_ir, *spill_ir;
+    float *state_ir;
     StateLayout lay;
 };
 
@@ -163,6 +162,19 @@ hipError_t launch_finalize_ir(const StateLayout &lay, const float4 *state, const
                               uint8_t *eligible, hipStream_t st);
 hipError_t launch_select(const float *pair_score, const uint8_t *eligible, int batch, int n_layers,
                          int n_select, int32_t *out_pairs, int32_t *out_count, hipStream_t st);
+
+// Workgroups of the matrix-core kernels that run side by side on one XCD (32 CUs, one 4 MB L2) are dealt
+// a PATCH of one unit's (row tile, key split) grid: patch_rows() row tiles by 32 / patch_rows() key
+// splits.  The workgroups of a patch row read the same query rows and those of a patch column the same
+// keys, at about the same time, so most of both streams is found in the L2 and comes from HBM once per
+// patch instead of once per workgroup.  The patch shape used is the one that divides the unit's grid;
+// patch_rows() returns 0 if none does (then workgroups are numbered row tile first, as without patches).
+__host__ __device__ inline int patch_rows(int n_row_tiles, int n_split)
+{
+    for (int pr = 8; pr >= 1; pr >>= 1)
+        if (n_row_tiles % pr == 0 && n_split % (32 / pr) == 0) return pr;
+    return 0;
+}
 
 // Index (in float4 records) of the record of partial p of row r of unit u
 // (u = b * Hkv + kv head; r = head-in-group * Tq + t) for layer l.

@@ -67,6 +67,7 @@ struct Cfg {
     static constexpr int PPR = D / 8;              // 16-byte pieces per row
     static constexpr int RPI = 64 / PPR;           // rows covered by one 1 KB wave-instruction
     static constexpr int SLOT_BYTES = CH * D * 2;
+    static constexpr int SLOT_ALIGN = SLOT_BYTES < 16384 ? SLOT_BYTES : 16384;
     static constexpr int NLD = CH * PPR / THREADS; // direct-to-LDS loads per thread per chunk
     static constexpr int QBYTES = 32 * D * 2;      // the 32 query rows of one wave row
     static constexpr int NQI = 32 / RPI;           // wave-instructions that copy them
@@ -130,10 +131,10 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     constexpr int NLD = C::NLD, PPR = C::PPR, NBLK = C::NBLK, RPI = C::RPI, PF = C::PF;
     // (the larger alignment puts the ring first in the workgroup's LDS, within reach of the
     // 16-bit offset field of the operand reads)
-    __shared__ __attribute__((aligned(16384))) unsigned char ring0[C::SLOT_BYTES];
-    __shared__ __attribute__((aligned(16384))) unsigned char ring1[C::SLOT_BYTES];
-    __shared__ __attribute__((aligned(16384))) unsigned char ring2[NC > 2 ? C::SLOT_BYTES : 16];
-    __shared__ __attribute__((aligned(16384))) unsigned char ring3[NC > 2 ? C::SLOT_BYTES : 16];
+    __shared__ __attribute__((aligned(C::SLOT_ALIGN))) unsigned char ring0[C::SLOT_BYTES];
+    __shared__ __attribute__((aligned(C::SLOT_ALIGN))) unsigned char ring1[C::SLOT_BYTES];
+    __shared__ __attribute__((aligned(C::SLOT_ALIGN))) unsigned char ring2[NC > 2 ? C::SLOT_BYTES : 16];
+    __shared__ __attribute__((aligned(C::SLOT_ALIGN))) unsigned char ring3[NC > 2 ? C::SLOT_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char qlds[C::WR * C::QBYTES];
     __shared__ float4 part[C::NW][64];   // every lane's record of the last step (m, Z, N2, C)
     __shared__ float part_ir[IR ? C::NW : 1][64];   // ... and its Zir
@@ -150,9 +151,26 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
     const int wr = wave / WK, wk = wave % WK, half = lane >> 5, l32 = lane & 31;
 
-    const int wg = xcd_remap(blockIdx.x, gridDim.x);
     const int nrt = p.lay.n_row_tiles, nsplit = p.lay.n_split;
-    const int rt = wg % nrt, sp = (wg / nrt) % nsplit, u = wg / (nrt * nsplit);
+    int rt, sp, u;
+    {
+        // the XCD's next workgroup in its contiguous range of logical ids; inside a unit the ids run patch
+        // by patch (see patch_rows()), inside a patch row tile first
+        const int w = xcd_remap(blockIdx.x, gridDim.x);
+        const int per_unit = nrt * nsplit, r = w % per_unit;
+        u = w / per_unit;
+        const int pr = patch_rows(nrt, nsplit);
+        if (pr) {
+            const int ps = 32 / pr, j = r % 32, pt = r / 32, prt = pt % (nrt / pr), psp = pt / (nrt / pr);
+            rt = prt * pr + j % pr;
+            sp = psp * ps + j / pr;
+        } else {
+            rt = r % nrt;
+            sp = r / nrt;
+        }
+    }
+    // where this workgroup's records go: by (unit, key split, row tile), whatever order the workgroups run in
+    const int wg = (u * nsplit + sp) * nrt + rt;
     const int b = u / p.Hkv, kvh = u % p.Hkv;
     const int L = p.L, S = p.S, Rk = p.lay.rows_per_unit;
 
@@ -342,9 +360,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         return a;
     };
 
-    // per-lane running records between key tiles (only when the split spans several tiles)
-    float4 *spill = p.spill;
-    auto spill_index = [&](int l) -> size_t { return ((((size_t)wg * L + l) * C::NW + wave) << 6) + lane; };
+    // Splits that span several key tiles: a row's running record (layer l, all keys so far) is the row
+    // record the merge below stores after every tile; at the next tile ONE of the row's partials -- the
+    // first half-wave of the first wave along the keys -- takes it up again, the others start empty.
+    const bool carries = wk == 0 && half == 0;
+    const size_t row_rec = (size_t)wg * L * C::R_WG + wr * 32 + l32;   // + l * R_WG: this lane's row, layer l
 
     float e[NBLK][16];
 #pragma unroll
@@ -376,7 +396,7 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
     // the merge costs no barrier of its own: at the end of a step every lane posts its record
     // in LDS; after the next chunk barrier the first wave of each wave row brings the partials
     // of its rows onto their common exponent, adds them in a fixed order and stores the row
-    // records.  The cross term of partial p carries the exponents of two layers: gprev[p] is
+    // records (after every tile: the stored record is also the running record the next tile starts from).  The cross term of partial p carries the exponents of two layers: gprev[p] is
     // the factor that took p's exponent of the previous layer onto that layer's merged one.
     float gprev[2 * WK];
 #pragma unroll
@@ -412,7 +432,6 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
         // keys of this tile to be masked out: past the end of the split, or (causal reading) past
         // the own position of some row of this wave
         const bool ragged = tile_key0 + C::KT > key_end || (p.causal && __any(tile_key0 + C::KT > row_end));
-        const bool last_tile = tile == ntiles - 1;
 
         for (int l = 0; l < L; ++l, ++step) {
             const float4 rec = rec_pre;
@@ -455,13 +474,14 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                     mg_on = false;
                 }
                 if (c == 0) {
-                    // The next step's running record was written L-1 steps ago (by this lane).
+                    // The next step's running record was stored L-2 steps ago or earlier (by this lane, in
+                    // merge_rows).
                     rec_pre = make_float4(kMInit, 0.f, 0.f, 0.f);
                     rec_ir_pre = 0.f;
-                    if (tn_ > 0 && has_next) {
-                        if (L < 4) __builtin_amdgcn_s_waitcnt(wait_vm(0));   // (then it may still be on its way)
-                        rec_pre = spill[spill_index(ln)];
-                        if (IR) rec_ir_pre = p.spill_ir[spill_index(ln)];
+                    if (tn_ > 0 && has_next && carries) {
+                        if (L < 5) __builtin_amdgcn_s_waitcnt(wait_vm(0));   // (then it may still be on its way)
+                        rec_pre = p.state[row_rec + (size_t)ln * C::R_WG];
+                        if (IR) rec_ir_pre = p.state_ir[row_rec + (size_t)ln * C::R_WG];
                     }
                 }
                 if (c == NC - 1) read_q();   // every wave has the old rows in use no more
@@ -608,16 +628,11 @@ __global__ __launch_bounds__(C::THREADS, 2) void sim_mfma_kernel(SimParams p)
                 out.w = fmaf(rec.w, F * f_prev, tc);
                 f_prev = F;
             }
-            if (!last_tile) {
-                spill[spill_index(l)] = out;
-                if (IR) p.spill_ir[spill_index(l)] = out_ir;
-            } else {
-                // ---- post this lane's record; the merge follows during the next step
-                part[wave][lane] = out;
-                if (IR) part_ir[wave][lane] = out_ir;
-                mg_l = l;
-                mg_on = true;
-            }
+            // ---- post this lane's record; the merge follows during the next step
+            part[wave][lane] = out;
+            if (IR) part_ir[wave][lane] = out_ir;
+            mg_l = l;
+            mg_on = true;
         }
     }
     // the last step's merge
