@@ -33,7 +33,7 @@ int check_shape(const krul_shape_t *s)
 }
 
 
-int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
+int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir, bool plain_keys)
 {
     const int rc = check_shape(s);
     if (rc != KRUL_OK) return rc;
@@ -73,7 +73,14 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
             else { y.variant = kMfmaMid; y.wr = 2; y.wk = 4; y.rb = 1; kt = 512; }
         } else {
             const long long w = B * Hkv * ((Rk + 127) / 128) * ((S + 255) / 256);
-            if (w <= 128) { y.variant = kMfmaWideShort; y.wr = 4; y.wk = 2; y.rb = 1; kt = 128; }
+            // Many query rows on a large problem: 256 x 256 tiles (two 32-row blocks per wave, the previous layer's
+            // exponentials kept as binary16 pairs) move a third fewer bytes per logit and read half the operands.
+            // Taken when the rows fill 256-row tiles well and there are two rounds of workgroups or more.
+            const long long nrt_big = (Rk + 255) / 256, w_big = B * Hkv * nrt_big * ((S + 255) / 256);
+            const bool big = plain_keys && !want_ir && !(s->flags & KRUL_FLAG_CAUSAL) && s->head_dim == 128 &&
+                             nrt_big * 256 * 7 <= Rk * 8 && w_big >= 512;
+            if (big) { y.variant = kMfmaBig; y.wr = 4; y.wk = 2; y.rb = 2; kt = 256; }
+            else if (w <= 128) { y.variant = kMfmaWideShort; y.wr = 4; y.wk = 2; y.rb = 1; kt = 128; }
             else { y.variant = kMfmaWide; y.wr = 4; y.wk = 2; y.rb = 1; kt = 256; }
         }
         const long long r_wg = y.wr * y.rb * 32;
@@ -81,17 +88,18 @@ int make_plan(const krul_shape_t *s, Plan *pl, bool want_ir)
         const long long units = B * Hkv * nrt;
         const long long tiles = (S + kt - 1) / kt;
         // the wide tile's workgroups are resident one per CU: aim for one round of them
-        const long long target = (y.variant == kMfmaWide || y.variant == kMfmaWideShort) ? kTargetWorkgroups / 2 : kTargetWorkgroups;
+        const bool wide = y.variant == kMfmaWide || y.variant == kMfmaWideShort || y.variant == kMfmaBig;
+        const long long target = wide ? kTargetWorkgroups / 2 : kTargetWorkgroups;
         long long want = (target + units - 1) / units;
         // The narrow tiles are bound by the stream of keys: there a split of several tiles, which
         // parks its running records in memory between tiles, costs a quarter of the bandwidth (a decode
         // step over 131072 tokens: 57 % of 8 TB/s against 74 % with one tile per split), and the
         // partial records stay below 1 % of the key bytes.  So: one tile per split, up to 1024 splits.
-        if (y.variant != kMfmaWide && y.variant != kMfmaWideShort && want < 1024) want = 1024;
+        if (!wide && want < 1024) want = 1024;
         // The wide tile on a large problem: four key splits (or more) per row tile, so that the workgroups
         // running side by side on an XCD form patches of 8 row tiles x 4 key splits (patch_rows()) and share
         // both their query rows and their keys through the L2 -- as long as a split keeps four tiles or more
-        if (y.variant == kMfmaWide && want < 4 && tiles >= 16 && nrt % 8 == 0) want = 4;
+        if ((y.variant == kMfmaWide || y.variant == kMfmaBig) && want < 4 && tiles >= 16 && nrt % 8 == 0) want = 4;
         if (want < 1 || (s->flags & KRUL_FLAG_SINGLE_SPLIT)) want = 1;
         long long nsplit = want < tiles ? want : tiles;
         const long long tps = (tiles + nsplit - 1) / nsplit;
@@ -217,7 +225,7 @@ int run_similarity(const krul_shape_t *shape, const void *q, const void *k, floa
                    const SelectArgs *sel = nullptr)
 {
     Plan pl;
-    const int rc = make_plan(shape, &pl, ir);
+    const int rc = make_plan(shape, &pl, ir, k != nullptr && !kl && !kp);
     if (rc != KRUL_OK) return rc;
     if (!q || (accumulate ? !head_score : !pair_score)) return KRUL_EINVAL;
     if (ir && (shape->flags & KRUL_FLAG_CAUSAL)) return KRUL_EUNSUPPORTED;
@@ -317,9 +325,10 @@ int krul_calibration_copy(const void *src, void *dst, size_t bytes, void *stream
 
 size_t krul_pair_similarity_workspace(const krul_shape_t *shape)
 {
-    Plan pl;
-    if (make_plan(shape, &pl) != KRUL_OK) return 0;
-    return pl.total_bytes;
+    // enough for the call on dense keys and for the calls on keys read in place (their plans may differ)
+    Plan pl, pl_dense;
+    if (make_plan(shape, &pl) != KRUL_OK || make_plan(shape, &pl_dense, false, true) != KRUL_OK) return 0;
+    return pl.total_bytes > pl_dense.total_bytes ? pl.total_bytes : pl_dense.total_bytes;
 }
 
 int krul_pair_similarity(const krul_shape_t *shape, const void *q, const void *k,
@@ -371,7 +380,7 @@ int krul_pair_similarity_static(const krul_shape_t *shape, const void *q, const 
                                 float *pair_score, float *head_score, float *pair_dist, void *stream)
 {
     Plan pl;
-    const int rc = make_plan(shape, &pl);
+    const int rc = make_plan(shape, &pl, false, true);
     if (rc != KRUL_OK) return rc;
     if (pl.total_bytes > (size_t)KRUL_STATIC_SCRATCH_BYTES) return KRUL_ESCRATCH;
     void *ptr = nullptr;

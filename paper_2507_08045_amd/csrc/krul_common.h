@@ -38,6 +38,7 @@ enum Variant : int {
     kMfmaSlimShort = 5,  // bf16 MFMA,  32 rows x 256 keys (1x4 waves, two workgroups per CU)
     kMfmaMidShort = 6,   // bf16 MFMA,  64 rows x 128 keys (2x2 waves)
     kMfmaWideShort = 7,  // bf16 MFMA, 128 rows x 128 keys (4x2 waves)
+    kMfmaBig = 8,        // bf16 MFMA, 256 rows x 256 keys (4x2 waves, two 32-row blocks per wave): krul_mfma_big.hip
 };
 
 // How the state records of one launch are laid out; used by the producer kernels
@@ -65,7 +66,9 @@ struct Plan {
 
 // Host: choose kernel and decomposition for a validated shape.  Returns a
 // krul_status_t.
-int make_plan(const krul_shape_t *s, Plan *plan, bool want_ir = false);
+// plain_keys: the keys are dense and no mask or Initial-Recent test is asked for -- what the many-query kernel
+// (kMfmaBig) takes; the plan (and so the workspace) may differ with it.
+int make_plan(const krul_shape_t *s, Plan *plan, bool want_ir = false, bool plain_keys = false);
 
 struct SimParams {
     const void *q;
@@ -141,6 +144,7 @@ hipError_t launch_select_all(const float *score, int closer_is_smaller, const ui
 // Launchers (each returns hipError_t of the launch).
 hipError_t launch_sim_generic(const SimParams &p, int dtype, int n_workgroups, hipStream_t st);
 hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st);
+hipError_t launch_sim_mfma_big(const SimParams &p, int n_workgroups, hipStream_t st);
 // accumulate: add the sums over rows to head_cos / head_dist (head_dist may then be null) and write no
 // pair scores; otherwise write the means and the pair scores (pair_dist may be null: no distances;
 // pair_cos may be null: head values only, head_dist filled iff pair_dist is set).

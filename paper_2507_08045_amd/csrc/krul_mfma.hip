@@ -15,6 +15,8 @@ hipError_t launch_sim_mfma(const SimParams &p, int n_workgroups, hipStream_t st)
 {
     const bool d128 = p.d > 64;   // (head sizes below the kernel's ride in zero-padded LDS rows)
     switch (p.lay.variant) {
+    case kMfmaBig:
+        return launch_sim_mfma_big(p, n_workgroups, st);
     case kMfmaWide:
     case kMfmaWideShort:
         return d128 ? launch_sim_mfma_wide128(p, n_workgroups, st) : launch_sim_mfma_wide64(p, n_workgroups, st);
