@@ -124,6 +124,35 @@ def all_pairs_bench(args, kr, torch, w, q, k, shp):
     print(json.dumps(res))
 
 
+def micro_bench(args, kr, torch):
+    """The inner step of the similarity kernels with no memory traffic (krul_calibration_block): the floors
+    'matrix cores alone', 'vector units alone', 'both from one instruction stream' per 32 x 32 block of logits,
+    on one 8-wave workgroup per CU (two waves per SIMD).  Prints one JSON line."""
+    out = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    iters = 1500
+    res = {"metric": "block step of the similarity kernels, no memory traffic", "unit": "ns per 32x32 block of logits and SIMD",
+           "blocks_per_wave": "2 * row_blocks * %d" % iters, "waves_per_simd": 2, "results": {}}
+    names = {1: "mfma", 2: "valu", 3: "mfma+valu", 5: "lds+mfma", 7: "lds+mfma+valu"}
+    for rb in (1, 2):
+        for parts in (1, 2, 3, 5, 7):
+            for _ in range(2):
+                kr.calibration_block(rb, parts, iters, out)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                kr.calibration_block(rb, parts, iters, out)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 3
+            # two waves per SIMD, each 2 * rb * iters blocks
+            res["results"][f"row_blocks={rb} {names[parts]}"] = round(ms * 1e6 / (2 * 2 * rb * iters), 1)
+    # the matrix cores' own time for a block: 8 MFMAs x 32 cycles at the clock the chain ran at
+    res["note"] = ("a block is 8 MFMAs 32x32x16 (256 cycles of a SIMD's matrix core: 107 ns at 2.4 GHz) and the vector work "
+                   "of 16 logits per lane")
+    print(json.dumps(res))
+
+
 class _Shape:
     """Extents and names of the workload being timed (the numbers live in the device tensors)."""
     def __init__(self, **kw):
@@ -138,7 +167,8 @@ def load_inputs(name, torch, np):
     the inputs of the step before it in that cache."""
     import workloads
     if name == "C5":
-        q, k, info = workloads.config_device(name)
+        q, k, info = workloads.config_device(
+            name, progress=lambda b, n: print(f"bench.py: drew conversation {b + 1} of {n}", file=sys.stderr, flush=True))
         w = _Shape(**{f: info[f] for f in ("name", "B", "L", "Hq", "Hkv", "d", "S", "Tq", "dtype", "n_select")})
         return w, [(q, k)]
     ww = workloads.config(name)
@@ -173,6 +203,9 @@ def main():
     ap.add_argument("--all-pairs", action="store_true",
                     help="time the all-pairs reading instead (every two layers scored, then the greedy choice "
                          "over all of them); not the headline metric")
+    ap.add_argument("--micro", action="store_true",
+                    help="run the block-step calibration kernels instead (floors of the matrix cores, the vector units, "
+                         "and both together for the similarity kernels' inner step); not the headline metric")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run the library's plain copy kernel on MIB MiB a few times (a known-size "
                          "reference for rocprofv3 traffic counters)")
@@ -192,6 +225,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.micro:
+        micro_bench(args, kr, torch)
+        return
     w, sets = load_inputs(args.config, torch, np)
     q, k = sets[0]
     torch.cuda.synchronize()
@@ -264,7 +300,7 @@ def main():
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
         traffic_src = f"profiles/traffic_{w.name}.json (recorded by a rocprofv3 --pmc run, not by this run)"
-    kernel_name = "sim_mfma_kernel" if w.dtype == "bf16" and not (args.flags & 256) else "sim_generic_kernel"
+    kernel_name = "sim_generic_kernel" if args.flags & kr.KRUL_FLAG_GENERIC_KERNEL else kr.plan(shp)["kernel"]
     hbm = {"bound": "hbm", "achieved": bytes_alg / kern_s / 1e9, "peak": 8000.0, "unit": "GB/s",
            "frac": bytes_alg / kern_s / 1e9 / 8000.0, "algorithmic_bytes": bytes_alg}
     mfma = {"bound": "mfma", "achieved": flops_alg / kern_s / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
@@ -288,7 +324,7 @@ def main():
                                f"{w.dtype}, select {w.n_select} pairs", "score_elems": w.score_elems,
                    "outputs": "pair_score+head_score" + ("+pair_dist" if args.with_dist else "") + "+pairs",
                    "calls": "krul_pair_similarity + krul_select_pairs" if args.two_calls else "krul_pair_similarity_select",
-                   "input_buffer_sets": len(sets)},
+                   "input_buffer_sets": len(sets), "plan": kr.plan(shp)},
         "roofline": main_roof,
         "roofline_hbm": hbm, "roofline_mfma": mfma, "roofline_alu": alu,
         "selected_pairs": pairs.cpu().tolist()[0],

@@ -389,6 +389,27 @@ int krul_pair_similarity_timed(const krul_shape_t *shape, const void *q, const v
  */
 int krul_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/*
+ * Measurement aid: the inner step of the similarity kernels with no memory traffic, on 256 workgroups of 8
+ * waves (one per CU, two waves per SIMD).  Per 32-key x 32-row block of logits (head_dim 128) and wave: a chain
+ * of 8 MFMAs 32x32x16 bf16 (parts bit 0), the vector work of its 16 logits per lane -- scale-and-shift, exp2,
+ * sum of squares, cross term, binary16 copy -- (bit 1), the 8 operand reads from LDS (bit 2); parts is one of
+ * 1, 2, 3, 5, 7.  row_blocks (1 or 2): 32-row blocks per block of keys, as in the two forms of the kernel.  Every
+ * wave takes 2 * row_blocks * iters blocks.  Timed by the caller (events around the call), it gives the floors
+ * "matrix cores alone", "vector units alone", "both from one instruction stream" that the similarity kernels'
+ * times are read against.
+ *   out   device, 256 * 512 floats, scratch (keeps the work from being optimised away)
+ */
+int krul_calibration_block(int32_t row_blocks, int32_t parts, int32_t iters, float *out, void *stream);
+
+/*
+ * Measurement aid, host-only: which kernel form krul_pair_similarity takes for this shape on dense keys: 0 the
+ * portable vector-ALU kernel; 1 to 7 the matrix-core kernel's tile shapes (1 wide 128 rows x 256 keys, 2 mid
+ * 64 x 512, 3 slim 32 x 512, 4 slim with a deep ring, 5 / 6 / 7 the short forms of slim / mid / wide); 8 the
+ * many-query kernel (256 x 256).  Negative: a krul_status_t.  n_workgroups, n_key_splits: may be NULL.
+ */
+int krul_pair_similarity_plan(const krul_shape_t *shape, int32_t *n_workgroups, int32_t *n_key_splits);
+
 
 #ifdef __cplusplus
 }

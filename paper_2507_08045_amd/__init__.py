@@ -6,7 +6,7 @@ from .binding import (KRUL_BF16, KRUL_EDTYPE, KRUL_EINVAL, KRUL_ELAUNCH, KRUL_ES
                       KRUL_F16, KRUL_F32, KRUL_FLAG_CAUSAL, KRUL_FLAG_GENERIC_KERNEL, KRUL_FLAG_SINGLE_SPLIT,
                       KRUL_OK, KrulError, KrulKLayout, KrulKPages, KrulKeys, KrulShape, PagedKeys,
                       StridedKeys, all_pairs_similarity, all_pairs_similarity_in_place,
-                      all_pairs_workspace_bytes, calibration_copy, lib,
+                      all_pairs_workspace_bytes, calibration_block, calibration_copy, lib, plan,
                       make_shape, n_select_from_ratio, pair_scores_from_sums, pair_similarity,
                       pair_similarity_accumulate, pair_similarity_accumulate_in_place, pair_similarity_ir,
                       pair_similarity_ir_in_place, pair_similarity_paged, pair_similarity_select, pair_similarity_static,

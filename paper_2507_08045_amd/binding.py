@@ -115,6 +115,10 @@ def lib() -> ctypes.CDLL:
         L.krul_select_pairs.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
         L.krul_calibration_copy.restype = ctypes.c_int
         L.krul_calibration_copy.argtypes = [vp, vp, sz, vp]
+        L.krul_calibration_block.restype = ctypes.c_int
+        L.krul_calibration_block.argtypes = [i32, i32, i32, vp, vp]
+        L.krul_pair_similarity_plan.restype = ctypes.c_int
+        L.krul_pair_similarity_plan.argtypes = [ctypes.POINTER(KrulShape), ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.krul_n_select_from_ratio.restype = i32
         L.krul_n_select_from_ratio.argtypes = [i32, ctypes.c_float]
         L.krul_strerror.restype = ctypes.c_char_p
@@ -150,6 +154,30 @@ def workspace_bytes(shape: KrulShape) -> int:
 
 def workspace_bytes_ir(shape: KrulShape) -> int:
     return int(lib().krul_pair_similarity_ir_workspace(ctypes.byref(shape)))
+
+
+KERNEL_FORMS = {0: "sim_generic_kernel", 1: "sim_mfma_kernel (wide, 128 x 256)", 2: "sim_mfma_kernel (mid, 64 x 512)",
+                3: "sim_mfma_kernel (slim, 32 x 512)", 4: "sim_mfma_kernel (slim, deep ring)",
+                5: "sim_mfma_kernel (slim short, 32 x 256)", 6: "sim_mfma_kernel (mid short, 64 x 128)",
+                7: "sim_mfma_kernel (wide short, 128 x 128)", 8: "sim_big_kernel (256 x 256)"}
+
+
+def plan(shape: KrulShape) -> dict:
+    """Which kernel form krul_pair_similarity takes for this shape on dense keys, and its grid."""
+    nwg, nsp = ctypes.c_int32(0), ctypes.c_int32(0)
+    v = int(lib().krul_pair_similarity_plan(ctypes.byref(shape), ctypes.byref(nwg), ctypes.byref(nsp)))
+    if v < 0:
+        raise KrulError(v)
+    return {"form": v, "kernel": KERNEL_FORMS.get(v, str(v)), "n_workgroups": nwg.value, "n_key_splits": nsp.value}
+
+
+def calibration_block(row_blocks: int, parts: int, iters: int, out: torch.Tensor) -> None:
+    """krul_calibration_block on the current stream (out: float32 GPU tensor of 256 * 512 elements)."""
+    if not out.is_cuda or out.dtype != torch.float32 or out.numel() < 256 * 512:
+        raise ValueError("out must be a float32 GPU tensor of at least 131072 elements")
+    rc = lib().krul_calibration_block(int(row_blocks), int(parts), int(iters), _dev_ptr(out), ctypes.c_void_p(_stream_ptr()))
+    if rc != KRUL_OK:
+        raise KrulError(rc)
 
 
 def _stream_ptr() -> int:

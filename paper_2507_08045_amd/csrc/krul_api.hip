@@ -323,6 +323,16 @@ int krul_calibration_copy(const void *src, void *dst, size_t bytes, void *stream
     return hipGetLastError() == hipSuccess ? KRUL_OK : KRUL_ELAUNCH;
 }
 
+int krul_pair_similarity_plan(const krul_shape_t *shape, int32_t *n_workgroups, int32_t *n_key_splits)
+{
+    Plan pl;
+    const int rc = make_plan(shape, &pl, false, true);
+    if (rc != KRUL_OK) return rc;
+    if (n_workgroups) *n_workgroups = pl.n_workgroups;
+    if (n_key_splits) *n_key_splits = pl.lay.n_split;
+    return pl.lay.variant;
+}
+
 size_t krul_pair_similarity_workspace(const krul_shape_t *shape)
 {
     // enough for the call on dense keys and for the calls on keys read in place (their plans may differ)

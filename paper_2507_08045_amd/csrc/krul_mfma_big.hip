@@ -141,9 +141,9 @@ __global__ __launch_bounds__(512, 2) void sim_big_kernel(SimParams p)
     // a slot's place goes into the instruction's offset field.  The query rows are read at the same offsets plus
     // a wave-uniform distance that is added at the read (kept out of registers: see q_delta()).
     auto kaddr_of = [&](int ks) __attribute__((always_inline)) -> int {
-        int base = ka_base;
-        asm volatile("" : "+v"(base));   // (formed at the read: eight registers less over the loop)
-        return base ^ (ks << 5);
+        int flip = ks << 5;
+        asm volatile("" : "+s"(flip));   // (opaque: the offset is formed at the read, by one XOR, not kept over the loop)
+        return ka_base ^ flip;
     };
     bf16x8 qf[2][KS], aop[KS];
     auto read_q = [&](int rb) __attribute__((always_inline)) {

@@ -157,11 +157,12 @@ def scaled(name: str, *, S=None, Tq=None, L=None, batch=None, seed=None) -> Work
                 n_select=max(1, L // 4), rho_k=rho, seed=seed, **kw)
 
 
-def config_device(name: str, *, device="cuda", batch=None, seed=None):
+def config_device(name: str, *, device="cuda", batch=None, seed=None, progress=None):
     """The same recipe drawn ON THE DEVICE with torch's seeded Philox generator, for configurations whose
     host draw takes minutes (C5: 22.5 GiB).  Returns (q, k, info): q [B, L, Hq, Tq, d] and k [B, L, Hkv, S, d]
     as device tensors of the storage type, info = dict(name, shape fields, n_select, rho_k [B, L-1, Hkv] numpy,
-    rho_q, sinks).  The numbers differ from config()'s numpy draw (another generator), the recipe does not."""
+    rho_q, sinks).  The numbers differ from config()'s numpy draw (another generator), the recipe does not.
+    progress: called with (conversation index, B) after each conversation is drawn."""
     import torch
     B, L, Hq, Hkv, d, S, Tq, dtype, n_select = CONFIGS[name]
     if batch is not None:
@@ -201,6 +202,8 @@ def config_device(name: str, *, device="cuda", batch=None, seed=None):
                 qc = rho_q * qc + cq * torch.randn((Hq, Tq, d), generator=g, device=device, dtype=torch.float32)
             q[b, l] = qc.to(tdt)
             k[b, l] = (kc if gain is None else kc * gain).to(tdt)
+        if progress is not None:
+            progress(b, B)
     info = dict(name=name, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, dtype=dtype, n_select=n_select,
                 rho_k=rho, rho_q=rho_q, sinks=sinks, score_elems=B * (L - 1) * Hq * Tq * S)
     return q, k, info
