@@ -124,29 +124,32 @@ def all_pairs_bench(args, kr, torch, w, q, k, shp):
     print(json.dumps(res))
 
 
+def block_step_ns(kr, torch, rb, parts, iters=1500):
+    """ns per 32 x 32 block of logits and SIMD of krul_calibration_block(rb, parts): two waves per SIMD, each
+    2 * rb * iters blocks."""
+    out = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        kr.calibration_block(rb, parts, iters, out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        kr.calibration_block(rb, parts, iters, out)
+    e1.record()
+    torch.cuda.synchronize()
+    return round(e0.elapsed_time(e1) / 3 * 1e6 / (2 * 2 * rb * iters), 1)
+
+
 def micro_bench(args, kr, torch):
     """The inner step of the similarity kernels with no memory traffic (krul_calibration_block): the floors
     'matrix cores alone', 'vector units alone', 'both from one instruction stream' per 32 x 32 block of logits,
     on one 8-wave workgroup per CU (two waves per SIMD).  Prints one JSON line."""
-    out = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
-    iters = 1500
     res = {"metric": "block step of the similarity kernels, no memory traffic", "unit": "ns per 32x32 block of logits and SIMD",
-           "blocks_per_wave": "2 * row_blocks * %d" % iters, "waves_per_simd": 2, "results": {}}
+           "blocks_per_wave": "2 * row_blocks * 1500", "waves_per_simd": 2, "results": {}}
     names = {1: "mfma", 2: "valu", 3: "mfma+valu", 5: "lds+mfma", 7: "lds+mfma+valu"}
     for rb in (1, 2):
         for parts in (1, 2, 3, 5, 7):
-            for _ in range(2):
-                kr.calibration_block(rb, parts, iters, out)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(3):
-                kr.calibration_block(rb, parts, iters, out)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / 3
-            # two waves per SIMD, each 2 * rb * iters blocks
-            res["results"][f"row_blocks={rb} {names[parts]}"] = round(ms * 1e6 / (2 * 2 * rb * iters), 1)
+            res["results"][f"row_blocks={rb} {names[parts]}"] = block_step_ns(kr, torch, rb, parts)
     # the matrix cores' own time for a block: 8 MFMAs x 32 cycles at the clock the chain ran at
     res["note"] = ("a block is 8 MFMAs 32x32x16 (256 cycles of a SIMD's matrix core: 107 ns at 2.4 GHz) and the vector work "
                    "of 16 logits per lane")
@@ -307,12 +310,19 @@ def main():
             "frac": flops_alg / kern_s / 1e12 / 2500.0, "algorithmic_flops": flops_alg}
     alu = {"bound": "alu", "achieved": valu_alg / kern_s / 1e12, "peak": VALU_PEAK_TOPS, "unit": "T lane-op/s",
            "frac": valu_alg / kern_s / 1e12 / VALU_PEAK_TOPS, "algorithmic_lane_ops": valu_alg}
-    # Matrix and vector instructions of a SIMD do not run side by side on this chip (measured: bench.py --micro, the
-    # block step takes the SUM of its MFMA time and its vector time), so the compute floor of the method is the sum of
-    # the two floors, not their maximum.  Reported beside the three plain roofs.
-    serial_floor_s = flops_alg / 2500e12 + valu_alg / (VALU_PEAK_TOPS * 1e12)
-    serial = {"bound": "mfma+alu (serialised)", "floor_us": serial_floor_s * 1e6, "frac": serial_floor_s / kern_s,
-              "note": "floor = algorithmic MFMA flops / 2.5 PFLOP/s + 5 vector issue slots per logit / 39.3 T lane-op/s, both at the 2.4 GHz peak clock"}
+    # What the method's own instruction mix allows, measured live: krul_calibration_block runs, per 32 x 32 block of
+    # logits, the same MFMA chain, the same operand reads from LDS and the vector work of 16 logits per lane, with no
+    # memory traffic, barriers or merges, on every SIMD of the chip.  The matrix and the vector instructions of a SIMD
+    # overlap only in part, so this floor lies well above the MFMA roof's; reported beside the three plain roofs.
+    mix = None
+    if w.dtype == "bf16":
+        rb = 2 if kr.plan(shp)["form"] == 8 else 1
+        ns = block_step_ns(kr, torch, rb, 7)
+        blocks_per_simd = w.B * w.L * w.Hq * w.Tq * w.S / 1024.0 / 1024.0
+        mix = {"bound": "instruction mix (measured block step)", "ns_per_block_and_simd": ns, "row_blocks_per_wave": rb,
+               "floor_us": blocks_per_simd * ns * 1e-3, "frac": blocks_per_simd * ns * 1e-9 / kern_s,
+               "note": "floor = 32x32 blocks of logits per SIMD x the block step measured by krul_calibration_block "
+                       "(MFMA chain + LDS operand reads + vector work, no memory traffic) in this run"}
     # The roof that binds this workload: the one whose floor time (algorithmic work / peak) is longest.  The matrix
     # cores bind the many-query configurations (C4, C5), the HBM stream of keys the few-query ones (C2, C3, D*);
     # the vector units' floor is reported beside them (matrix and vector instructions share a wave's issue slots).
@@ -332,7 +342,7 @@ def main():
                    "calls": "krul_pair_similarity + krul_select_pairs" if args.two_calls else "krul_pair_similarity_select",
                    "input_buffer_sets": len(sets), "plan": kr.plan(shp)},
         "roofline": main_roof,
-        "roofline_hbm": hbm, "roofline_mfma": mfma, "roofline_alu": alu, "roofline_mfma_plus_alu": serial,
+        "roofline_hbm": hbm, "roofline_mfma": mfma, "roofline_alu": alu, "roofline_instruction_mix": mix,
         "selected_pairs": pairs.cpu().tolist()[0],
     }
     if not args.no_cpu_baseline:

@@ -30,7 +30,8 @@ __global__ __launch_bounds__(512, 2) void calibration_block_kernel(float *out, i
     f32x16 acc[RB];
     cal_h2 e2[RB][2][8];
     for (int r = 0; r < RB; ++r) {
-        for (int v = 0; v < 16; ++v) acc[r][v] = seed * 0.001f * (v + r);
+        // (no two of these values are equal or a fixed distance apart, so that no exponential below can serve twice)
+        for (int v = 0; v < 16; ++v) acc[r][v] = seed * 0.001f * (float)((v * v + 3 * v + 1) * (r + 1)) + 1e-4f * lane;
         for (int b = 0; b < 2; ++b)
             for (int i = 0; i < 8; ++i) e2[r][b][i] = cal_h2{(_Float16)(seed * 0.1f), (_Float16)(seed * 0.2f)};
     }
@@ -39,9 +40,11 @@ __global__ __launch_bounds__(512, 2) void calibration_block_kernel(float *out, i
     const float cs = 0.127f;
     const int a_base = (lane & 31) * 256 + (((lane >> 5) ^ (lane & 15)) << 4) + (wave & 1) * 8192;
     for (int it = 0; it < iters; ++it) {
-        const float negm = -seed * 0.01f - (float)it * 1e-6f;   // (moves every turn: nothing of the vector work is loop-invariant)
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
+            // (moves every turn and with b: nothing of the vector work is loop-invariant or shared between blocks)
+            const float negm = -seed * 0.01f - (float)(2 * it + b) * 1.3e-6f;
+            if (!(FL & 4)) asm volatile("" : "+v"(aop[0]));   // (opaque: no chain is the same as last turn's)
             if (FL & 4) {
                 const unsigned char *slot = lds + ((it * 2 + b) & 3) * 16384;
 #pragma unroll
