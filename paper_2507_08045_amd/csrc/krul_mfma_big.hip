@@ -357,8 +357,10 @@ __global__ __launch_bounds__(512, 2) void sim_big_kernel(SimParams p)
             // (K3b) 12 or more; at c = 3 (K0b and the last Q) 2.  In the first step the chunks come from the
             // prologue, back to back: 4 after K1b.
             if (c == 0) {
-                if (step == 0) __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(4));
-                else __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(7));
+                // (4 in every step: the three Q that make the 7 landed before the last barrier of the step before, so
+                // nothing more is waited for; and with one count on every path the compiler adds no wait of its own
+                // in front of the first operand read)
+                __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(4));
             } else if (c == 1) {
                 __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(8));
             } else if (c == 2) {
