@@ -51,8 +51,8 @@ __global__ __launch_bounds__(512, 2) void sim_big_kernel(SimParams p)
     __shared__ __attribute__((aligned(16384))) unsigned char ring3[SLOT_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char qlds[4 * QWR_BYTES];
     __shared__ float4 part[8][2][64];   // every lane's record of the last step, per row block
-    __shared__ __attribute__((aligned(1024))) float4 runl[4][64];   // per wave row: the running records (all tiles before this one) of its 64 rows
-    __shared__ float gl[4][5][64];      // per wave row, partial and row: last step's merge factors
+    __shared__ __attribute__((aligned(1024))) float4 runl[8][64];   // per wave: the running records (all tiles before this one) of the 32 rows it merges
+    __shared__ float gl[8][5][32];      // per wave and partial: last step's merge factors
     auto slot_ptr = [&](int i) __attribute__((always_inline)) -> unsigned char * {
         switch (i & 3) {
         case 0: return ring0;
@@ -176,65 +176,46 @@ __global__ __launch_bounds__(512, 2) void sim_big_kernel(SimParams p)
     // ---- merge of a row's partials, one step late: the tile's four (two half-waves, two waves along the keys) and,
     // from the second tile on, the row's running record over the tiles before (copied into runl a step ahead).
     // The result is stored as the row record: the final one after the last tile, the running one before.  The
-    // two waves of a wave row take turns: one of them merges all 64 rows of the wave row (a lane per row: row
-    // block = half-wave), the other one the step after, so that a merge keeps every lane busy and each SIMD -- it
-    // holds waves (wr, wk) and (wr + 2, wk) -- has one merge per step.  gl: factors that took each partial's
-    // exponent of the previous layer onto that layer's merged one (the cross term carries two layers' exponents);
-    // kept in LDS -- registers are what this kernel is short of -- and, like runl, handed from one wave to the other
-    // across the step's barriers.
-    const int turn0 = (wk ^ (wr >> 1)) & 1;   // this wave merges in the steps of this parity
-    gl[wr][wk * 2][lane] = 1.f;
-    gl[wr][wk * 2 + 1][lane] = 1.f;
-    if (wk == 0) gl[wr][4][lane] = 1.f;
-    const size_t my_rec = (size_t)wg * L * R_WG + wr * 64;   // + l * R_WG: first of the wave row's 64 rows
-    // (The partials and the running record are read by hand-placed LDS reads: left to the compiler, one of these
-    // reads loses track of which LDS object it touches, is taken for a read of a copy's destination, and gets an
-    // s_waitcnt vmcnt(0) in front -- which waits for every key chunk in flight, once per step.  Both are complete
-    // here: the partials since the barrier, the running record since the wait before the last step's last
-    // barrier.)
-    auto lds_addr = [](const void *q) -> unsigned {
-        return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void *)q;
-    };
+    // two waves of a wave row share the work: wave (wr, wk) merges row block wk.  gl: factors that took each
+    // partial's exponent of the previous layer onto that layer's merged one (the cross term carries two layers'
+    // exponents); kept in LDS -- registers are what this kernel is short of.
+    if (half == 0)
+#pragma unroll
+        for (int i = 0; i < 5; ++i) gl[wave][i][l32] = 1.f;
+    const size_t my_rec = (size_t)wg * L * R_WG + wr * 64 + wk * 32;   // + l * R_WG: first of the 32 rows this wave merges
     auto merge_rows = [&](int l_of, bool with_run) __attribute__((always_inline)) {
-        unsigned pa[5];
+        if (half == 0) {   // (one lane per row)
+            const float4 *pr[5];
 #pragma unroll
-        for (int pi = 0; pi < 4; ++pi) pa[pi] = lds_addr(&part[wr * 2 + (pi >> 1)][half][(pi & 1) * 32 + l32]);
-        pa[4] = lds_addr(&runl[wr][lane]);
-        float mx[5];
-        asm volatile("ds_read_b32 %0, %5\n\tds_read_b32 %1, %6\n\tds_read_b32 %2, %7\n\tds_read_b32 %3, %8\n\t"
-                     "ds_read_b32 %4, %9\n\ts_waitcnt lgkmcnt(0)"
-                     : "=&v"(mx[0]), "=&v"(mx[1]), "=&v"(mx[2]), "=&v"(mx[3]), "=&v"(mx[4])
-                     : "v"(pa[0]), "v"(pa[1]), "v"(pa[2]), "v"(pa[3]), "v"(pa[4])
-                     : "memory");
-        float M = fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3]));
-        if (with_run) M = fmaxf(M, mx[4]);
-        float zs = 0.f, ns = 0.f, cc = 0.f;
+            for (int pi = 0; pi < 4; ++pi) pr[pi] = &part[wr * 2 + (pi >> 1)][wk][(pi & 1) * 32 + l32];
+            pr[4] = &runl[wave][l32];
+            float M = pr[0]->x;
 #pragma unroll
-        for (int pi = 0; pi < 5; ++pi) {
-            if (pi == 4 && !with_run) {
-                gl[wr][pi][lane] = 0.f;
-                break;
+            for (int pi = 1; pi < 4; ++pi) M = fmaxf(M, pr[pi]->x);
+            if (with_run) M = fmaxf(M, pr[4]->x);
+            float zs = 0.f, ns = 0.f, cc = 0.f;
+#pragma unroll
+            for (int pi = 0; pi < 5; ++pi) {
+                if (pi == 4 && !with_run) {
+                    gl[wave][pi][l32] = 0.f;
+                    break;
+                }
+                const float4 v = *pr[pi];
+                const float f = __builtin_amdgcn_exp2f(v.x - M);
+                zs = fmaf(v.y, f, zs);
+                ns = fmaf(v.z, f * f, ns);
+                cc = fmaf(v.w, f * gl[wave][pi][l32], cc);
+                gl[wave][pi][l32] = f;
             }
-            float vy, vz, vw;   // the record's Z, N2, C (its m is mx[pi])
-            asm volatile("ds_read_b32 %0, %3 offset:4\n\tds_read_b32 %1, %3 offset:8\n\tds_read_b32 %2, %3 offset:12\n\t"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(vy), "=&v"(vz), "=&v"(vw)
-                         : "v"(pa[pi])
-                         : "memory");
-            const float f = __builtin_amdgcn_exp2f(mx[pi] - M);
-            zs = fmaf(vy, f, zs);
-            ns = fmaf(vz, f * f, ns);
-            cc = fmaf(vw, f * gl[wr][pi][lane], cc);
-            gl[wr][pi][lane] = f;
+            p.state[my_rec + l32 + (size_t)l_of * R_WG] = make_float4(M, zs, ns, cc);
         }
-        p.state[my_rec + lane + (size_t)l_of * R_WG] = make_float4(M, zs, ns, cc);
     };
-    // the running records of layer l_of of the wave row's 64 rows (1 KB) -> runl[wr], by one copy instruction;
-    // read past the L1 (one of the two waves stored them a tile ago)
+    // the running records of layer l_of of the 32 rows this wave merges (512 bytes) -> runl[wave], by one copy
+    // instruction; read past the L1 (this wave stored them a tile ago)
     auto fetch_run = [&](int l_of, bool live) __attribute__((always_inline)) {
         const uint16_t *src = uniform_ptr(reinterpret_cast<const uint16_t *>(p.state + my_rec + (size_t)l_of * R_WG));
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(src), 0, live ? 1024 : 0, 0x00020000);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(&runl[wr][0]), 16,
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(src), 0, live ? 512 : 0, 0x00020000);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(&runl[wave][0]), 16,
                                                  lane * 16, 0, 0, 1 /* glc */);
     };
     // ---- the end of a layer step for row block rb: post this lane's sums over the tile
@@ -351,16 +332,14 @@ __global__ __launch_bounds__(512, 2) void sim_big_kernel(SimParams p)
             // have landed, for every wave.  Loads return in order, so it is enough that no more are outstanding
             // than were issued after the ones needed.  A wave's copies over a step, in issue order (K: a key chunk
             // of the next step, two instructions a and b; Q: one of eight instructions for the next layer's query
-            // rows; R: the record store and copy of the merge, in the steps in which it is this wave's turn):
+            // rows; R: the record store and copy of the merge):
             //   (0,1) R R K0a Q K0b Q   (1,0) Q Q   (1,1) K1a Q K1b Q   (2,0) Q Q   (2,1) K2a K2b   (3,1) K3a K3b
             // After the chunk needed at c = 0 (K1b of the step before) came 7; at c = 1 (K2b) 8 or more; at c = 2
             // (K3b) 12 or more; at c = 3 (K0b and the last Q) 2.  In the first step the chunks come from the
             // prologue, back to back: 4 after K1b.
             if (c == 0) {
-                // (4 in every step: the three Q that make the 7 landed before the last barrier of the step before, so
-                // nothing more is waited for; and with one count on every path the compiler adds no wait of its own
-                // in front of the first operand read)
-                __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(4));
+                if (step == 0) __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(4));
+                else __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(7));
             } else if (c == 1) {
                 __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(8));
             } else if (c == 2) {
@@ -372,12 +351,11 @@ __global__ __launch_bounds__(512, 2) void sim_big_kernel(SimParams p)
             // ======== phase (c, 1): logits of row block 1 on chunk c beside the exponentials of (c, 0); the
             // operands of the next chunk replace this chunk's as the chain passes
             {
-                if (c == 0 && (step & 1) == turn0) {
-                    // (this wave's turn) The step before is complete in LDS: merge it, with its layer's running
-                    // record if its tile was not the first.  Then copy in the running record this step's merge
-                    // -- the other wave's, a step from now -- will need (stored L-1 steps ago or earlier, and that
-                    // wave has waited for its stores since; the reads of runl above have returned: the merge used
-                    // them).
+                if (c == 0) {
+                    // The step before is complete in LDS: merge it, with its layer's running record if its tile
+                    // was not the first.  Then copy in the running record this step's merge will need (stored
+                    // L-1 steps ago or earlier by this wave; the reads of runl above have returned: the merge
+                    // used them).
                     if (step > 0) merge_rows(l == 0 ? L - 1 : l - 1, (l == 0 ? tile - 1 : tile) > 0);
                     if (L < 5) __builtin_amdgcn_s_waitcnt(wait_vm(0));
                     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
@@ -436,7 +414,7 @@ __global__ __launch_bounds__(512, 2) void sim_big_kernel(SimParams p)
     // ---- the last step's merge
     __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));
     __builtin_amdgcn_s_barrier();
-    if ((nsteps & 1) == turn0) merge_rows(L - 1, ntiles > 1);
+    merge_rows(L - 1, ntiles > 1);
 }
 
 }  // namespace
