@@ -91,3 +91,42 @@ def test_identical_layers(G, oracle):
     # the cross term sees binary16 copies of one layer's exponentials: 2^-11 relative at most
     assert np.max(np.abs(got["head_score"][:, 0] - 1.0)) < 6e-4
     assert np.all(got["head_score"] <= 1.0 + 6e-4) and np.all(got["head_score"] > 0)
+
+
+def test_agrees_with_the_128_row_kernel(G, oracle):
+    # the same inputs through sim_mfma_kernel (a call that also asks for the Initial-Recent test never takes the
+    # many-query kernel): the two kernels' head scores differ by the rounding of the binary16 copies at most
+    import paper_2507_08045_amd as kr
+    w = workloads.make("big-7", B=4, L=4, Hq=8, Hkv=2, d=128, S=16384 - 100, Tq=64, dtype="bf16", rho_k=0.6, seed=87)
+    q, k = G.to_device(w)
+    sh = kr.KrulShape(4, 4, 8, 2, 128, 16384 - 100, 64, kr.KRUL_BF16, 0.0, 0)
+    assert kr.plan(sh)["form"] == 8
+    a = G.gpu_scores(q, k)["head_score"]
+    b = kr.pair_similarity_ir(q, k, gamma=0.5)["head_score"].cpu().numpy()
+    assert np.max(np.abs(a - b)) < 6e-4
+
+
+@pytest.mark.parametrize("seed", [201, 202, 203, 204])
+def test_seeded_random_shapes(G, oracle, seed):
+    # shapes drawn so that the plan takes the many-query kernel: rows per kv head from 230 up (ragged row tiles),
+    # ragged key tails, 2 to 5 layers, one to four kv heads; the oracle's cost bounds the sizes
+    import paper_2507_08045_amd as kr
+    rng = np.random.default_rng(seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    g = int(rng.choice([1, 2, 4]))
+    rows = int(rng.choice([230, 256, 500, 760, 1000]))          # rows per kv head wanted
+    Tq = max(1, rows // g)
+    Rk = g * Tq
+    nrt = (Rk + 255) // 256
+    assert nrt * 256 * 7 <= Rk * 8
+    L = int(rng.integers(2, 6))
+    B = int(rng.choice([1, 2]))
+    tiles = -(-512 // (B * Hkv * nrt)) + int(rng.integers(0, 3))   # 512 workgroup tiles or a few more
+    S = tiles * 256 - int(rng.integers(0, 255))
+    w = workloads.make(f"big-rand-{seed}", B=B, L=L, Hq=Hkv * g, Hkv=Hkv, d=128, S=S, Tq=Tq, dtype="bf16",
+                       rho_k=float(rng.uniform(0.3, 0.95)), seed=seed)
+    sh = kr.KrulShape(B, L, Hkv * g, Hkv, 128, S, Tq, kr.KRUL_BF16, 0.0, 0)
+    pl = kr.plan(sh)
+    print(f"[big-rand-{seed}] B={B} L={L} Hq/Hkv={Hkv * g}/{Hkv} S={S} Tq={Tq}: {pl}", flush=True)
+    assert pl["form"] == 8, pl
+    run_case(G, oracle, w)
