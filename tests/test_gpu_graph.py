@@ -19,8 +19,9 @@ def G():
 
 
 @pytest.mark.parametrize("shape", [dict(B=2, L=6, Hq=8, Hkv=2, d=128, S=900, Tq=40),      # wide tile, several splits
-                                   dict(B=3, L=5, Hq=8, Hkv=4, d=64, S=2300, Tq=2)],      # narrow tile
-                         ids=["prefill-chunk", "decode-step"])
+                                   dict(B=3, L=5, Hq=8, Hkv=4, d=64, S=2300, Tq=2),       # narrow tile
+                                   dict(B=4, L=4, Hq=8, Hkv=2, d=128, S=16384 - 50, Tq=64)],  # 256-row tiles (sim_big_kernel)
+                         ids=["prefill-chunk", "decode-step", "many-query"])
 def test_step_replays_from_a_graph(G, oracle, shape):
     import paper_2507_08045_amd as kr
     n_select = 2
