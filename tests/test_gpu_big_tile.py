@@ -130,3 +130,23 @@ def test_seeded_random_shapes(G, oracle, seed):
     print(f"[big-rand-{seed}] B={B} L={L} Hq/Hkv={Hkv * g}/{Hkv} S={S} Tq={Tq}: {pl}", flush=True)
     assert pl["form"] == 8, pl
     run_case(G, oracle, w)
+
+
+def test_accumulate_over_two_calls(G, oracle):
+    # two calls of 64 query tokens each over the same keys (no mask), accumulated and then averaged over the 128
+    # tokens, against one oracle pass over all 128: the accumulating calls take the many-query kernel too
+    import paper_2507_08045_amd as kr
+    w = workloads.make("big-8", B=4, L=3, Hq=8, Hkv=2, d=128, S=16384 - 9, Tq=128, dtype="bf16", rho_k=0.7, seed=88)
+    q, k = G.to_device(w)
+    sh = kr.KrulShape(4, 3, 8, 2, 128, 16384 - 9, 64, kr.KRUL_BF16, 0.0, 0)
+    assert kr.plan(sh)["form"] == 8
+    head_sum = torch.zeros((4, 2, 8), dtype=torch.float32, device="cuda")
+    dist_sum = torch.zeros_like(head_sum)
+    kr.pair_similarity_accumulate(q[:, :, :, :64].contiguous(), k, head_sum, dist_sum)
+    kr.pair_similarity_accumulate(q[:, :, :, 64:].contiguous(), k, head_sum, dist_sum)
+    out = kr.pair_scores_from_sums(head_sum, 128, dist_sum)
+    torch.cuda.synchronize()
+    want = oracle.pair_similarity(w.q, w.k)
+    G.assert_close(out["head_score"].cpu().numpy(), want["head_score"], G.TOL, "accumulated head_score")
+    G.assert_close(out["pair_score"].cpu().numpy(), want["pair_score"], G.TOL, "accumulated pair_score")
+    G.assert_close(out["pair_dist"].cpu().numpy(), want["pair_dist"], G.TOL, "accumulated pair_dist")
