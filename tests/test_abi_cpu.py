@@ -279,3 +279,54 @@ def test_binding_refuses_cpu_tensors(kr):
         kr.pair_similarity(q, k)
     with pytest.raises(ValueError):
         kr.select_pairs(torch.zeros((1, 3)), 1)
+
+
+def test_plan_for_the_benchmark_shapes(kr):
+    """krul_pair_similarity_plan is host logic: which kernel form and grid each benchmark shape gets."""
+    import workloads
+
+    def plan(name, **over):
+        B, L, Hq, Hkv, d, S, Tq, dt, _ = workloads.CONFIGS[name]
+        dtype = {"f32": kr.KRUL_F32, "bf16": kr.KRUL_BF16, "f16": kr.KRUL_F16}[dt]
+        a = dict(B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, S=S, Tq=Tq, flags=0)
+        a.update(over)
+        return kr.plan(kr.KrulShape(a["B"], a["L"], a["Hq"], a["Hkv"], a["d"], a["S"], a["Tq"], dtype, 0.0, a["flags"]))
+
+    assert plan("C1")["form"] == 0                                   # fp32: the portable kernel
+    c2 = plan("C2")
+    assert c2["form"] == 1 and c2["n_workgroups"] == 256 and c2["n_key_splits"] == 16
+    assert plan("C3")["form"] == 2                                   # 64 rows per kv head: the 64 x 512 tile
+    c4, c5 = plan("C4"), plan("C5")
+    # many query rows: 256 x 256 tiles, four key splits per row tile (patches of 8 row tiles x 4 splits)
+    assert c4["form"] == 8 and c4["n_key_splits"] == 4 and c4["n_workgroups"] == 8 * 32 * 4
+    assert c5["form"] == 8 and c5["n_key_splits"] == 4 and c5["n_workgroups"] == 64 * 8 * 4
+    assert plan("D1")["form"] in (3, 4) and plan("D2")["form"] in (3, 4) and plan("D3")["form"] == 5
+    # a mask keeps the many-query shapes on the 128-row kernel; the single-split flag changes the grid, not the kernel
+    assert plan("C4", flags=kr.KRUL_FLAG_CAUSAL)["form"] == 1
+    one = plan("C4", flags=kr.KRUL_FLAG_SINGLE_SPLIT)
+    assert one["form"] == 8 and one["n_key_splits"] == 1
+    # the workspace covers whichever plan the call takes
+    B, L, Hq, Hkv, d, S, Tq, _, _ = workloads.CONFIGS["C5"]
+    sh = kr.KrulShape(B, L, Hq, Hkv, d, S, Tq, kr.KRUL_BF16, 0.0, 0)
+    records = c5["n_workgroups"] * L * 256 * 16
+    assert kr.workspace_bytes(sh) >= records
+
+
+def test_static_entry_point_rejects_what_does_not_fit_before_any_gpu_work(kr):
+    lib = kr.lib()
+    import workloads
+    B, L, Hq, Hkv, d, S, Tq, _, _ = workloads.CONFIGS["C5"]
+    big = kr.KrulShape(B, L, Hq, Hkv, d, S, Tq, kr.KRUL_BF16, 0.0, 0)
+    assert kr.workspace_bytes(big) > kr.KRUL_STATIC_SCRATCH_BYTES
+    fake = ctypes.c_void_p(256)
+    rc = lib.krul_pair_similarity_static(ctypes.byref(big), fake, fake, fake, None, None, None)
+    assert rc == kr.KRUL_ESCRATCH
+    bad = kr.KrulShape(1, 1, 8, 2, 128, 64, 4, kr.KRUL_BF16, 0.0, 0)      # one layer: no pair
+    assert lib.krul_pair_similarity_static(ctypes.byref(bad), fake, fake, fake, None, None, None) == kr.KRUL_EINVAL
+
+
+def test_calibration_entry_points_reject_bad_arguments(kr):
+    lib = kr.lib()
+    assert lib.krul_calibration_block(3, 7, 10, ctypes.c_void_p(256), None) == kr.KRUL_EINVAL     # row blocks: 1 or 2
+    assert lib.krul_calibration_block(2, 7, 0, ctypes.c_void_p(256), None) == kr.KRUL_EINVAL      # no iterations
+    assert lib.krul_calibration_block(2, 7, 10, None, None) == kr.KRUL_EINVAL                     # no output
